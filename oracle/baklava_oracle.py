@@ -1,0 +1,278 @@
+"""CPU oracle for the ragged per-head KV-cache decode path (BaKlaVa, arXiv 2502.13176).
+
+TEST INFRASTRUCTURE ONLY.  This file is a plain, slow, fp64 statement of what
+the hot path computes.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import it; the product (the HIP library and its Python
+binding) never does, and this file imports nothing from the product.
+
+Each function cites the passage of the paper it follows.  Where the paper is
+silent the reading taken is stated in the docstring.
+
+Pins (see tests/test_oracle_*.py):
+  decode_attn            pure-Python brute force, closed forms, torch fp64 SDPA,
+                         shift/permutation invariances
+  score_accumulate       closed form sum = G per step
+  compact_select/apply   brute-force full sort, structural invariants
+  alloc_proportional     exact-rational water-filling, invariants
+  alloc_threshold        conservation + structure only: the paper prints no
+                         worked example of Algorithm 2 -> beyond those
+                         invariants PARITY UNPINNED
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+FRAC_BITS = 40  # fixed-point fraction bits of the proportional allocator's weights
+
+
+# ---------------------------------------------------------------------------
+# Budget allocation (host step, once per model)
+# ---------------------------------------------------------------------------
+
+def alloc_proportional(importance: Sequence[float], global_budget: int, lo: int, hi: int) -> List[int]:
+    """Budgets proportional to importance, clipped to [lo, hi], summing exactly to global_budget.
+
+    The paper assigns larger caches to more important KV heads (Methods,
+    "Assigning Memory Budgets to KV-Caches") but prints no proportional rule;
+    the benchmark workloads ask for one.  Reading taken, chosen so that integer
+    arithmetic alone decides every rounding:
+
+      w_i = max(1, floor(I_i / max(I) * 2^40))
+      x_i(lam) = floor(lam * w_i / 2^40),  f(lam) = sum_i clip(x_i, lo, hi)
+      lam* = largest integer lam with f(lam) <= B
+      b_i = clip(x_i(lam*), lo, hi); the B - sum(b) leftover tokens go, one
+      each, to the heads with lo <= x_i < hi having the largest
+      (lam*·w_i mod 2^40, w_i, -i).
+    """
+    imp = [float(v) for v in importance]
+    m = len(imp)
+    B = int(global_budget)
+    if m == 0 or lo < 0 or hi < lo:
+        raise ValueError("bad arguments")
+    if any((not math.isfinite(v)) or v <= 0.0 for v in imp):
+        raise ValueError("importance must be finite and positive")
+    if m * lo > B or m * hi < B:
+        raise ValueError("infeasible budget")
+    one = 1 << FRAC_BITS
+    top = max(imp)
+    w = [max(1, int(math.floor((v / top) * float(one)))) for v in imp]
+
+    def clip(x: int) -> int:
+        return lo if x < lo else (hi if x > hi else x)
+
+    def f(lam: int) -> int:
+        return sum(clip((lam * wi) >> FRAC_BITS) for wi in w)
+
+    lam_hi = ((hi << FRAC_BITS) // min(w)) + 1      # every x_i >= hi here
+    if f(lam_hi) <= B:
+        lam = lam_hi
+    else:
+        a, z = 0, lam_hi                            # f(a) <= B < f(z)
+        while z - a > 1:
+            mid = (a + z) // 2
+            if f(mid) <= B:
+                a = mid
+            else:
+                z = mid
+        lam = a
+    x = [(lam * wi) >> FRAC_BITS for wi in w]
+    b = [clip(xi) for xi in x]
+    left = B - sum(b)
+    elig = [i for i in range(m) if lo <= x[i] < hi]
+    assert 0 <= left <= len(elig)
+    elig.sort(key=lambda i: ((lam * w[i]) & (one - 1), w[i], -i), reverse=True)
+    for i in elig[:left]:
+        b[i] += 1
+    return b
+
+
+def alloc_threshold(importance: Sequence[float], size_in: Sequence[int], t: float, r: float) -> List[int]:
+    """Algorithm 2 (KV-cache memory reallocation by attention-head importance).
+
+    Caches whose importance is below t give up a fraction r of their current
+    size; what they free is shared by the k = min(n, m - n) most important of
+    the remaining caches (n = number of reduced caches).
+
+    Readings where the listing is ambiguous: the "all low" guard |L| > m-1
+    means |L| = m; an empty low set also returns the input unchanged (the
+    listing would divide 0 by 0); r is a fraction of the cache's size and the
+    reduction is floor(r*size); the top-k set is drawn from the caches that
+    were not reduced, ties to the lower index; the freed total F is split as
+    floor(F/k) each with the remainder going one token apiece to the most
+    important first; increased caches are not clipped to the context length.
+    """
+    imp = [float(v) for v in importance]
+    size = [int(s) for s in size_in]
+    m = len(imp)
+    if len(size) != m:
+        raise ValueError("length mismatch")
+    if not (0.0 <= r <= 1.0):
+        raise ValueError("r must be in [0,1]")
+    low = [i for i in range(m) if imp[i] < t]
+    n = len(low)
+    if n == m or n == 0:
+        return size
+    freed = 0
+    for i in low:
+        d = int(math.floor(r * size[i]))
+        size[i] -= d
+        freed += d
+    k = min(n, m - n)
+    lowset = set(low)
+    high = [i for i in range(m) if i not in lowset]
+    high.sort(key=lambda i: (-imp[i], i))
+    chosen = high[:k]
+    base, rem = divmod(freed, k)
+    for rank, j in enumerate(chosen):
+        size[j] += base + (1 if rank < rem else 0)
+    return size
+
+
+def layout(budget: Sequence[int], L: int, Hkv: int, batch: int, slack: int) -> Tuple[List[int], List[int], int]:
+    """Capacity and start offset (in tokens) of every cache, cache id c = (l*batch + b)*Hkv + h.
+
+    A cache of budget b_c has room for b_c + slack rows (the rows appended
+    between two compactions); offsets are the exclusive prefix sum.  Budgets
+    depend on (layer, head) only: they are a property of the model (Methods,
+    first paragraphs), so every sequence of the batch uses the same ones.
+    """
+    off, cap, total = [], [], 0
+    for l in range(L):
+        for b in range(batch):
+            for h in range(Hkv):
+                c = int(budget[l * Hkv + h]) + slack
+                off.append(total)
+                cap.append(c)
+                total += c
+    return off, cap, total
+
+
+# ---------------------------------------------------------------------------
+# Decode attention over one cache (Eq. 1 scaled dot-product attention, applied
+# to the single query row of Eq. 4 / Eq. 7 over the reduced cache)
+# ---------------------------------------------------------------------------
+
+def decode_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """softmax(q K^T / sqrt(D)) V for the G query heads sharing one KV head.
+
+    q [G, D], K [n, D], V [n, D], all fp64 holding the exact values of the
+    stored inputs.  The cache already contains the current token's row (the
+    concatenation [K'; K_t] of Eq. 7), and a decode query sees every row: no
+    mask.  Returns (out [G, D], p [G, n]).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    G, D = q.shape
+    n = K.shape[0]
+    if n == 0:
+        raise ValueError("attention over an empty cache")
+    out = np.zeros((G, D), dtype=np.float64)
+    p = np.zeros((G, n), dtype=np.float64)
+    for g in range(G):
+        s = (K @ q[g]) / math.sqrt(D)       # s_j = q_g . k_j / sqrt(D_h)
+        e = np.exp(s - np.max(s))
+        p[g] = e / np.sum(e)
+        out[g] = p[g] @ V
+    return out, p
+
+
+def score_accumulate(score: np.ndarray, p: np.ndarray) -> np.ndarray:
+    """Cumulative attention per cached token (the heavy-hitter statistic, Related Work:
+    eviction by cumulative attention).  For grouped-query attention the weights of the G
+    query heads sharing the cache are summed: score_j += sum_g p[g, j]."""
+    return np.asarray(score, dtype=np.float64) + np.sum(p, axis=0)
+
+
+# ---------------------------------------------------------------------------
+# Budget-enforcing eviction (f_evict, Eqs. 5-6: removed tokens vanish, the
+# survivors keep their order)
+# ---------------------------------------------------------------------------
+
+POLICY_SCORE = 0       # sink + recent + top-scored middle tokens
+POLICY_STREAMING = 1   # sink + most recent tokens only (the policy the paper evaluated with)
+
+
+def compact_select(score: np.ndarray, n: int, budget: int, sink: int, recent: int,
+                   policy: int = POLICY_SCORE) -> List[int]:
+    """Ascending list of the row indices that survive eviction down to `budget`.
+
+    n <= budget: nothing is evicted.  Otherwise the first `sink` rows and the
+    last `recent` rows always survive and the remaining budget - sink - recent
+    places go to the middle rows with the largest accumulated score; equal
+    scores: the older row (lower index) wins.  Scores are compared as fp32
+    values, the precision the kernel stores them in.  Streaming policy: sink
+    rows plus the budget - sink most recent rows.
+    """
+    if n <= budget:
+        return list(range(n))
+    if policy == POLICY_STREAMING:
+        if budget < sink:
+            raise ValueError("budget < sink")
+        recent = budget - sink
+    if budget < sink + recent:
+        raise ValueError("budget < sink + recent")
+    k = budget - sink - recent
+    mid = list(range(sink, n - recent))
+    s32 = np.asarray(score[:n], dtype=np.float32)
+    if np.any(np.isnan(s32)):
+        raise ValueError("NaN score")
+    mid.sort(key=lambda j: (-float(s32[j]), j))
+    kept = list(range(sink)) + mid[:k] + list(range(n - recent, n))
+    kept.sort()
+    return kept
+
+
+class Cache:
+    """One (sequence, layer, KV head) cache: rows in arrival order after eviction."""
+
+    def __init__(self, D: int):
+        self.K = np.zeros((0, D), dtype=np.float64)
+        self.V = np.zeros((0, D), dtype=np.float64)
+        self.score = np.zeros((0,), dtype=np.float64)
+        self.pos = np.zeros((0,), dtype=np.int64)
+
+    @property
+    def n(self) -> int:
+        return self.K.shape[0]
+
+    def append(self, k_row: np.ndarray, v_row: np.ndarray, token_pos: int) -> None:
+        """[K'; K_t], [V'; V_t] of Eq. 7: the new token's row goes last, its score starts at 0."""
+        self.K = np.vstack([self.K, np.asarray(k_row, dtype=np.float64)[None, :]])
+        self.V = np.vstack([self.V, np.asarray(v_row, dtype=np.float64)[None, :]])
+        self.score = np.append(self.score, 0.0)
+        self.pos = np.append(self.pos, np.int64(token_pos))
+
+    def load(self, K: np.ndarray, V: np.ndarray, score: np.ndarray, pos: np.ndarray) -> None:
+        self.K = np.array(K, dtype=np.float64)
+        self.V = np.array(V, dtype=np.float64)
+        self.score = np.array(score, dtype=np.float64)
+        self.pos = np.array(pos, dtype=np.int64)
+
+    def compact(self, budget: int, sink: int, recent: int, policy: int = POLICY_SCORE) -> List[int]:
+        """Apply f_evict for every row not selected; returns the kept indices."""
+        kept = compact_select(self.score, self.n, budget, sink, recent, policy)
+        self.K = self.K[kept]
+        self.V = self.V[kept]
+        self.score = self.score[kept]
+        self.pos = self.pos[kept]
+        return kept
+
+
+def decode_step(cache: Cache, q: np.ndarray, k_new, v_new, token_pos: int, step_index: int,
+                budget: int, sink: int, recent: int, interval: int, track_scores: bool,
+                policy: int = POLICY_SCORE):
+    """One decode step on one cache: append -> attention -> score update -> compaction when
+    step_index is a multiple of `interval`.  Returns (out [G,D], p [G,n], kept or None)."""
+    if k_new is not None:
+        cache.append(k_new, v_new, token_pos)
+    out, p = decode_attn(q, cache.K, cache.V)
+    if track_scores:
+        cache.score = score_accumulate(cache.score, p)
+    kept = None
+    if interval > 0 and step_index % interval == 0:
+        kept = cache.compact(budget, sink, recent, policy)
+    return out, p, kept

@@ -1,0 +1,199 @@
+/*
+ * libbaklava -- ragged per-head KV-cache decode path for AMD MI355X (gfx950).
+ *
+ * The method (BaKlaVa, arXiv 2502.13176) gives every (layer, KV head) cache its
+ * own token budget from a one-time importance profile, so at decode time each
+ * head's cache has a different length.  This library holds the part of that
+ * method that runs once per generated token:
+ *
+ *   host, once      per-cache budgets from importance scores
+ *   device, per step  append the new K/V row, single-query attention over every
+ *                     ragged cache, optional accumulation of attention weights
+ *   device, every few steps  eviction down to each cache's own budget
+ *
+ * Plain C ABI: pointers and sizes only.  Every pointer is marked HOST or DEVICE.
+ * All functions return a status code (0 = BAKLAVA_OK); nothing aborts, throws or
+ * prints.  Device entry points enqueue work on the caller's stream and return
+ * without synchronising.  The caller owns every byte of device memory; the
+ * library allocates only small host-side structures inside baklava_ctx.
+ *
+ * Notation: L layers, Hkv KV heads, G = Hq/Hkv query heads per KV head (query
+ * head hq reads KV head hq / G), D head dimension, `batch` sequences.
+ * Cache id  c = (layer * batch + b) * Hkv + h  (layer-major).
+ * Budget id i = layer * Hkv + h  (budgets are a property of the model, the same
+ * for every sequence).
+ */
+#ifndef BAKLAVA_H
+#define BAKLAVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  BAKLAVA_OK = 0,
+  BAKLAVA_EINVAL = 1,      /* null pointer, bad shape / dtype / option, misaligned pointer          */
+  BAKLAVA_EINFEASIBLE = 2, /* budgets cannot be met: m*lo > B, m*hi < B, budget < sink + recent     */
+  BAKLAVA_ECAPACITY = 3,   /* an append would exceed a cache's capacity; workspace too small        */
+  BAKLAVA_EHIP = 4,        /* a HIP runtime call failed; see baklava_last_hip_error()               */
+  BAKLAVA_ESTATE = 5       /* call order violated, e.g. attention over an empty cache               */
+};
+
+enum { BAKLAVA_BF16 = 0, BAKLAVA_F32 = 1 };
+enum { BAKLAVA_POLICY_SCORE = 0, BAKLAVA_POLICY_STREAMING = 1 };
+
+/* Static text for a status code. */
+const char* baklava_strerror(int status);
+/* hipError_t value of the last failed HIP call made by this library on the calling thread. */
+int baklava_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Host only.  No GPU is touched; usable on a machine without one.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Budgets proportional to importance (Methods, "Assigning Memory Budgets to KV-Caches": more
+ * important heads get larger caches), clipped to [lo, hi] and rounded so that they sum to
+ * global_budget exactly.  The paper prints no proportional rule; the rule used is integer-only:
+ *   w_i = max(1, floor(I_i / max(I) * 2^40)),  x_i(lam) = floor(lam * w_i / 2^40),
+ *   lam = largest integer with sum_i clip(x_i) <= B,  b_i = clip(x_i(lam)),
+ *   leftover tokens go one each to heads with lo <= x_i < hi in decreasing order of
+ *   (lam*w_i mod 2^40, w_i, lower index first).
+ * importance  HOST [m], finite and > 0.   budget_out  HOST [m].
+ * Errors: EINVAL (null, m <= 0, lo < 0, hi < lo, non-finite or non-positive importance),
+ *         EINFEASIBLE (m*lo > global_budget or m*hi < global_budget).
+ */
+int baklava_alloc_proportional(const double* importance, int32_t m, int64_t global_budget,
+                               int32_t lo, int32_t hi, int32_t* budget_out);
+
+/*
+ * Algorithm 2 (KV-cache memory reallocation based on attention-head importance): caches with
+ * importance < t shrink by floor(r * size); the freed tokens are shared by the
+ * k = min(n, m - n) most important of the other caches (n = number shrunk), floor(F/k) each and
+ * the remainder one apiece to the most important first.  No cache below t, or all below t:
+ * output equals input.  Increased sizes are not clipped.
+ * importance HOST [m], size_in HOST [m], budget_out HOST [m] (may alias size_in).
+ * Errors: EINVAL (null, m <= 0, r outside [0,1], negative size).
+ */
+int baklava_alloc_threshold(const double* importance, int32_t m, const int32_t* size_in,
+                            double t, double r, int32_t* budget_out);
+
+/*
+ * Arena layout replacing the per-head cache object of the paper's implementation (Methods,
+ * last paragraph before Algorithm 1): cache c gets capacity budget[layer*Hkv+h] + slack rows at
+ * token offset off[c] = sum of the capacities before it.
+ * budget HOST [L*Hkv];  off_out HOST int64 [L*batch*Hkv];  cap_out HOST int32 [L*batch*Hkv];
+ * total_tokens_out HOST scalar = rows each arena plane must hold.
+ * Errors: EINVAL (null, non-positive shape, negative budget or slack, capacity overflow of int32).
+ */
+int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int32_t batch, int32_t slack,
+                   int64_t* off_out, int32_t* cap_out, int64_t* total_tokens_out);
+
+/* ------------------------------------------------------------------------------------------
+ * Device.
+ * ------------------------------------------------------------------------------------------ */
+
+typedef struct baklava_ctx baklava_ctx;
+
+typedef struct {
+  int32_t L, Hq, Hkv, D, batch;
+  int32_t dtype;          /* BAKLAVA_BF16 or BAKLAVA_F32: element type of k, v and of q / k_new / v_new */
+  int32_t sink, recent;   /* rows at the front / back of a cache that eviction never removes        */
+  int32_t policy;         /* BAKLAVA_POLICY_*                                                        */
+  int32_t track_scores;   /* 1: decode_attn adds each token's attention weights to `score`          */
+  void* k;                /* DEVICE [total_tokens, D] row-major, 16-byte aligned                     */
+  void* v;                /* DEVICE [total_tokens, D]                                                */
+  float* score;           /* DEVICE [total_tokens] accumulated attention per cached token            */
+  int32_t* pos;           /* DEVICE [total_tokens] original sequence position of each cached token   */
+  const int64_t* off;     /* DEVICE [n_caches] first row of cache c                                  */
+  const int32_t* cap;     /* DEVICE [n_caches] rows cache c can hold                                 */
+  int32_t* len;           /* DEVICE [n_caches] live rows of cache c (authoritative copy)             */
+  const int32_t* budget;  /* DEVICE [L*Hkv]                                                          */
+  void* workspace;        /* DEVICE scratch, 256-byte aligned, baklava_workspace_bytes() bytes       */
+  size_t workspace_bytes;
+} baklava_desc;
+
+/*
+ * Bytes of device workspace a context with this description needs (split partials, work-item
+ * table, kept-index lists, and the logit stash when track_scores is set).  Pointer fields of
+ * `desc` are ignored.  cap_host HOST [n_caches].  Returns 0 on invalid arguments.
+ */
+size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host);
+
+/*
+ * Creates a context.  The *_host arrays are copies of the device tables in `desc` (the library
+ * keeps a host mirror of the lengths so that no call reads anything back from the device);
+ * len_host may be NULL for all-empty caches, in which case the caller must have zeroed desc->len
+ * or call baklava_reset.  Writes the work-item table into the workspace with a synchronous copy.
+ * Supported shapes: D in {64, 128}; Hq a multiple of Hkv with Hq/Hkv <= 16 (<= 8 for F32);
+ * sink, recent >= 0.
+ * Errors: EINVAL, EINFEASIBLE (some budget < sink + recent under POLICY_SCORE, or < sink under
+ * POLICY_STREAMING), ECAPACITY (workspace_bytes too small, or len > cap), EHIP.
+ */
+int baklava_create(const baklava_desc* desc, const int64_t* off_host, const int32_t* cap_host,
+                   const int32_t* len_host, const int32_t* budget_host, baklava_ctx** out);
+int baklava_destroy(baklava_ctx* ctx);
+
+/* Tuning knobs (tests sweep them; results must not depend on them beyond rounding order). */
+enum {
+  BAKLAVA_OPT_CHUNK_TOKENS = 1, /* rows per split-K work item (multiple of 64, >= 64)               */
+  BAKLAVA_OPT_KERNEL = 2        /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
+};
+int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
+
+/* Empties every cache: device len <- 0 (fill kernel on `stream`), host mirror <- 0. */
+int baklava_reset(baklava_ctx* ctx, void* stream);
+
+/*
+ * Declares the live lengths after the caller has filled arena rows itself (a prefill).
+ * len_host HOST [n_caches]; copied to the device table on `stream` and to the host mirror.
+ * Errors: EINVAL, ECAPACITY (len > cap).
+ */
+int baklava_set_lengths(baklava_ctx* ctx, const int32_t* len_host, void* stream);
+
+/*
+ * Appends the current token's key and value row to every cache of one layer -- the
+ * concatenations [K'; K_t], [V'; V_t] of Eq. 7.  The row's score starts at 0 and its pos is
+ * token_pos.  k_new, v_new DEVICE [batch, Hkv, D] in the context's dtype.
+ * Errors: EINVAL, ECAPACITY (some cache of the layer is full; nothing is enqueued).
+ */
+int baklava_append(baklava_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
+                   int32_t token_pos, void* stream);
+
+/*
+ * Single-query attention over the reduced caches (Eq. 7, i.e. Eq. 1 with one query row per
+ * head and the evicted rows absent) for layers [layer_begin, layer_begin + layer_count):
+ *   out[hq] = softmax(q[hq] . K_c^T / sqrt(D)) V_c,  c = the cache of KV head hq / G.
+ * q   DEVICE [layer_count, batch, Hq, D] in the context's dtype, 16-byte aligned.
+ * out DEVICE [layer_count, batch, Hq, D] fp32, fully overwritten.
+ * With track_scores, score[j] += sum over the G query heads of the softmax weight of row j.
+ * Accumulation is fp32 throughout.
+ * Errors: EINVAL, ESTATE (a cache in range is empty).
+ */
+int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                        const void* q, float* out, void* stream);
+
+/*
+ * Eviction down to budget (f_evict, Eqs. 5-6: evicted rows vanish, survivors keep their order)
+ * for every cache of the layer range whose length exceeds its budget.  Survivors: the first
+ * `sink` rows, the last `recent` rows, and the budget - sink - recent middle rows with the
+ * largest score (equal scores: the older row wins; scores compare as fp32, -0 == +0; NaN
+ * scores are not supported).  POLICY_STREAMING keeps the sink rows and the budget - sink most
+ * recent ones.  K, V, score and pos rows are moved in place; len <- min(len, budget).
+ * kept_idx_out DEVICE int32 [total_tokens] or NULL: for each cache in range, entries
+ * off[c] .. off[c] + new_len - 1 receive the old cache-local row index of each surviving row.
+ * Rows at index >= new_len are unspecified afterwards.
+ */
+int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                    int32_t* kept_idx_out, void* stream);
+
+/* Host mirror of the lengths; len_host_out HOST [n_caches].  No device access. */
+int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAKLAVA_H */

@@ -1,0 +1,234 @@
+"""ctypes binding of libbaklava: argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels; nothing here
+computes.  PyTorch tensors are used as device memory (`.data_ptr()`) and for
+the current stream.  Importing this module does not load the library; the
+first call does, and fails loudly if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbaklava.so")
+
+OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
+BF16, F32 = 0, 1
+POLICY_SCORE, POLICY_STREAMING = 0, 1
+OPT_CHUNK_TOKENS, OPT_KERNEL = 1, 2
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+
+EXPORTS = [
+    "baklava_strerror", "baklava_last_hip_error", "baklava_alloc_proportional",
+    "baklava_alloc_threshold", "baklava_layout", "baklava_workspace_bytes", "baklava_create",
+    "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
+    "baklava_append", "baklava_decode_attn", "baklava_compact", "baklava_lengths",
+]
+
+
+class BaklavaError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({strerror(status)})")
+
+
+class Desc(C.Structure):
+    _fields_ = [
+        ("L", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("batch", C.c_int32),
+        ("dtype", C.c_int32), ("sink", C.c_int32), ("recent", C.c_int32), ("policy", C.c_int32),
+        ("track_scores", C.c_int32),
+        ("k", C.c_void_p), ("v", C.c_void_p), ("score", C.c_void_p), ("pos", C.c_void_p),
+        ("off", C.c_void_p), ("cap", C.c_void_p), ("len", C.c_void_p), ("budget", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2502_13176_amd.build). "
+            "There is no fallback path.")
+    L = C.CDLL(LIB_PATH)
+    i32p, i64p, f64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_double)
+    L.baklava_strerror.restype = C.c_char_p
+    L.baklava_strerror.argtypes = [C.c_int]
+    L.baklava_last_hip_error.restype = C.c_int
+    L.baklava_alloc_proportional.argtypes = [f64p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, i32p]
+    L.baklava_alloc_threshold.argtypes = [f64p, C.c_int32, i32p, C.c_double, C.c_double, i32p]
+    L.baklava_layout.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i64p, i32p, i64p]
+    L.baklava_workspace_bytes.restype = C.c_size_t
+    L.baklava_workspace_bytes.argtypes = [C.POINTER(Desc), i32p]
+    L.baklava_create.argtypes = [C.POINTER(Desc), i64p, i32p, i32p, i32p, C.POINTER(C.c_void_p)]
+    L.baklava_destroy.argtypes = [C.c_void_p]
+    L.baklava_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
+    L.baklava_reset.argtypes = [C.c_void_p, C.c_void_p]
+    L.baklava_set_lengths.argtypes = [C.c_void_p, i32p, C.c_void_p]
+    L.baklava_append.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    L.baklava_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.baklava_compact.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.baklava_lengths.argtypes = [C.c_void_p, i32p]
+    for name in EXPORTS:
+        if name not in ("baklava_strerror", "baklava_workspace_bytes"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return lib().baklava_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise BaklavaError(status, what)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a: np.ndarray, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+# ---------------------------------------------------------------------------
+# host-only calls
+# ---------------------------------------------------------------------------
+
+def alloc_proportional(importance: Sequence[float], global_budget: int, lo: int, hi: int) -> List[int]:
+    imp = np.ascontiguousarray(importance, dtype=np.float64)
+    out = np.zeros(len(imp), dtype=np.int32)
+    _check(lib().baklava_alloc_proportional(_p(imp, C.c_double), len(imp), int(global_budget), int(lo),
+                                            int(hi), _p(out, C.c_int32)), "baklava_alloc_proportional")
+    return out.tolist()
+
+
+def alloc_threshold(importance: Sequence[float], size_in: Sequence[int], t: float, r: float) -> List[int]:
+    imp = np.ascontiguousarray(importance, dtype=np.float64)
+    size = _i32(size_in)
+    out = np.zeros(len(imp), dtype=np.int32)
+    _check(lib().baklava_alloc_threshold(_p(imp, C.c_double), len(imp), _p(size, C.c_int32), float(t),
+                                         float(r), _p(out, C.c_int32)), "baklava_alloc_threshold")
+    return out.tolist()
+
+
+def layout(budget: Sequence[int], L: int, Hkv: int, batch: int, slack: int):
+    b = _i32(budget)
+    n = L * Hkv * batch
+    off = np.zeros(n, dtype=np.int64)
+    cap = np.zeros(n, dtype=np.int32)
+    total = C.c_int64(0)
+    _check(lib().baklava_layout(_p(b, C.c_int32), L, Hkv, batch, slack, _p(off, C.c_int64),
+                                _p(cap, C.c_int32), C.byref(total)), "baklava_layout")
+    return off, cap, int(total.value)
+
+
+# ---------------------------------------------------------------------------
+# device context
+# ---------------------------------------------------------------------------
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class Arena:
+    """Device memory of a ragged KV arena plus a libbaklava context over it.
+
+    Holds torch tensors only to keep the memory alive; all work goes through
+    the C-ABI calls.
+    """
+
+    def __init__(self, L: int, Hq: int, Hkv: int, D: int, batch: int, dtype: str, budget: Sequence[int],
+                 slack: int, sink: int, recent: int, policy: int = POLICY_SCORE, track_scores: bool = False,
+                 device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.L, self.Hq, self.Hkv, self.D, self.batch = L, Hq, Hkv, D, batch
+        self.G = Hq // Hkv
+        self.dtype = dtype
+        self.device = torch.device(device)
+        self.budget_host = _i32(budget)
+        self.off_host, self.cap_host, self.total_tokens = layout(budget, L, Hkv, batch, slack)
+        self.n_caches = L * batch * Hkv
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        dev = self.device
+        self.k = torch.zeros((self.total_tokens, D), dtype=tdt, device=dev)
+        self.v = torch.zeros((self.total_tokens, D), dtype=tdt, device=dev)
+        self.score = torch.zeros((self.total_tokens,), dtype=torch.float32, device=dev)
+        self.pos = torch.zeros((self.total_tokens,), dtype=torch.int32, device=dev)
+        self.off = torch.from_numpy(self.off_host).to(dev)
+        self.cap = torch.from_numpy(self.cap_host).to(dev)
+        self.len = torch.zeros((self.n_caches,), dtype=torch.int32, device=dev)
+        self.budget = torch.from_numpy(self.budget_host).to(dev)
+
+        d = Desc()
+        d.L, d.Hq, d.Hkv, d.D, d.batch = L, Hq, Hkv, D, batch
+        d.dtype = BF16 if dtype == "bf16" else F32
+        d.sink, d.recent, d.policy, d.track_scores = sink, recent, policy, int(bool(track_scores))
+        ws_bytes = lib().baklava_workspace_bytes(C.byref(d), _p(self.cap_host, C.c_int32))
+        if ws_bytes == 0:
+            raise BaklavaError(EINVAL, "baklava_workspace_bytes")
+        self.workspace = torch.zeros((ws_bytes,), dtype=torch.uint8, device=dev)
+        d.k, d.v = self.k.data_ptr(), self.v.data_ptr()
+        d.score, d.pos = self.score.data_ptr(), self.pos.data_ptr()
+        d.off, d.cap, d.len, d.budget = (self.off.data_ptr(), self.cap.data_ptr(), self.len.data_ptr(),
+                                         self.budget.data_ptr())
+        d.workspace, d.workspace_bytes = self.workspace.data_ptr(), ws_bytes
+        self.desc = d
+        torch.cuda.synchronize(dev)
+        ctx = C.c_void_p()
+        _check(lib().baklava_create(C.byref(d), _p(self.off_host, C.c_int64), _p(self.cap_host, C.c_int32),
+                                    None, _p(self.budget_host, C.c_int32), C.byref(ctx)), "baklava_create")
+        self.ctx = ctx
+
+    def close(self) -> None:
+        if getattr(self, "ctx", None):
+            lib().baklava_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- thin wrappers with the C names ------------------------------------------------
+    def set_option(self, option: int, value: int) -> None:
+        _check(lib().baklava_set_option(self.ctx, option, int(value)), "baklava_set_option")
+
+    def reset(self, stream=None) -> None:
+        _check(lib().baklava_reset(self.ctx, _stream_ptr(stream)), "baklava_reset")
+
+    def set_lengths(self, len_host: Sequence[int], stream=None) -> None:
+        a = _i32(len_host)
+        _check(lib().baklava_set_lengths(self.ctx, _p(a, C.c_int32), _stream_ptr(stream)), "baklava_set_lengths")
+
+    def append(self, layer: int, k_new, v_new, token_pos: int, stream=None) -> None:
+        _check(lib().baklava_append(self.ctx, layer, k_new.data_ptr(), v_new.data_ptr(), int(token_pos),
+                                    _stream_ptr(stream)), "baklava_append")
+
+    def decode_attn(self, layer_begin: int, layer_count: int, q, out, stream=None) -> None:
+        _check(lib().baklava_decode_attn(self.ctx, layer_begin, layer_count, q.data_ptr(), out.data_ptr(),
+                                         _stream_ptr(stream)), "baklava_decode_attn")
+
+    def compact(self, layer_begin: int, layer_count: int, kept_idx_out=None, stream=None) -> None:
+        ptr = kept_idx_out.data_ptr() if kept_idx_out is not None else None
+        _check(lib().baklava_compact(self.ctx, layer_begin, layer_count, ptr, _stream_ptr(stream)),
+               "baklava_compact")
+
+    def lengths(self) -> np.ndarray:
+        out = np.zeros(self.n_caches, dtype=np.int32)
+        _check(lib().baklava_lengths(self.ctx, _p(out, C.c_int32)), "baklava_lengths")
+        return out

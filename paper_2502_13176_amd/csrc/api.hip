@@ -1,0 +1,334 @@
+// C-ABI entry points of libbaklava (device part): context, split-K schedule, launches.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "baklava.h"
+#include "common.h"
+
+using namespace baklava;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  g_last_hip_error = (int)e;
+  return false;
+}
+
+constexpr int kMinChunk = 64;
+constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
+constexpr int kDefaultChunk = 1024;
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
+  int64_t n = 0;
+  for (int64_t c = 0; c < n_caches; ++c) n += std::max<int64_t>(1, ((int64_t)cap[c] + chunk - 1) / chunk);
+  return n;
+}
+
+struct WorkspacePlan {
+  size_t items, cib, part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, total;
+  int64_t max_items;
+};
+
+bool shape_ok(const baklava_desc* d) {
+  if (!d) return false;
+  if (d->L <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->batch <= 0) return false;
+  if (d->D != 64 && d->D != 128) return false;
+  if (d->dtype != BAKLAVA_BF16 && d->dtype != BAKLAVA_F32) return false;
+  if (d->Hq % d->Hkv) return false;
+  const int G = d->Hq / d->Hkv;
+  if (G > 16 || (d->dtype == BAKLAVA_F32 && G > 8)) return false;
+  if (d->dtype == BAKLAVA_BF16 && G > 8 && d->D != 128) return false;
+  if (d->sink < 0 || d->recent < 0) return false;
+  if (d->policy != BAKLAVA_POLICY_SCORE && d->policy != BAKLAVA_POLICY_STREAMING) return false;
+  if ((int64_t)d->L * d->batch * d->Hkv > INT32_MAX) return false;
+  return true;
+}
+
+WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
+  WorkspacePlan w{};
+  const int64_t n_caches = (int64_t)d->L * d->batch * d->Hkv;
+  const int G = d->Hq / d->Hkv;
+  int64_t total_tokens = 0;
+  for (int64_t c = 0; c < n_caches; ++c) total_tokens += cap[c];
+  w.max_items = count_items(cap, n_caches, kSizingChunk);
+  size_t o = 0;
+  w.items = o;       o = align256(o + (size_t)w.max_items * sizeof(Item));
+  w.cib = o;         o = align256(o + (size_t)(n_caches + 1) * 4);
+  w.part_o = o;      o = align256(o + (size_t)w.max_items * G * d->D * 4);
+  w.part_ml = o;     o = align256(o + (size_t)w.max_items * G * 2 * 4);
+  w.final_ml = o;    o = align256(o + (size_t)n_caches * G * 2 * 4);
+  w.logits = o;      o = align256(o + (d->track_scores ? (size_t)total_tokens * G * 4 : 0));
+  w.kept = o;        o = align256(o + (size_t)total_tokens * 4);
+  w.info = o;        o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
+  w.order_all = o;   o = align256(o + (size_t)n_caches * 4);
+  w.order_layer = o; o = align256(o + (size_t)n_caches * 4);
+  w.total = o;
+  return w;
+}
+
+}  // namespace
+
+struct baklava_ctx {
+  baklava_desc d;
+  int64_t n_caches;
+  int32_t cpl;  // caches per layer
+  int32_t G;
+  int32_t row_bytes;
+  std::vector<int64_t> off;
+  std::vector<int32_t> cap, len, budget;
+  int32_t chunk;
+  int32_t kernel_pref;
+  std::vector<int32_t> cib;  // cache -> first item
+  int64_t n_items;
+  WorkspacePlan plan;
+  char* ws;
+};
+
+namespace {
+
+// Cuts every cache into runs of `chunk` rows over its whole capacity.  The table depends on the
+// capacities only, so it is uploaded once; the kernels clamp each run to the live length.
+int build_schedule(baklava_ctx* ctx, int chunk) {
+  std::vector<Item> items;
+  std::vector<int32_t> cib(ctx->n_caches + 1);
+  items.reserve((size_t)count_items(ctx->cap.data(), ctx->n_caches, chunk));
+  for (int64_t c = 0; c < ctx->n_caches; ++c) {
+    cib[c] = (int32_t)items.size();
+    const int32_t cap = ctx->cap[c];
+    const int32_t n_runs = std::max(1, (cap + chunk - 1) / chunk);
+    for (int32_t s = 0; s < n_runs; ++s) {
+      Item it;
+      it.c = (int32_t)c;
+      it.start = s * chunk;
+      it.count = std::max(0, std::min(chunk, cap - s * chunk));
+      it.slot = (int32_t)items.size();
+      items.push_back(it);
+    }
+  }
+  cib[ctx->n_caches] = (int32_t)items.size();
+  if ((int64_t)items.size() > ctx->plan.max_items) return BAKLAVA_ECAPACITY;
+  if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items, items.data(), items.size() * sizeof(Item),
+                        hipMemcpyHostToDevice)))
+    return BAKLAVA_EHIP;
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib, cib.data(), cib.size() * 4, hipMemcpyHostToDevice)))
+    return BAKLAVA_EHIP;
+  ctx->cib.swap(cib);
+  ctx->n_items = (int64_t)items.size();
+  ctx->chunk = chunk;
+  return BAKLAVA_OK;
+}
+
+bool range_ok(const baklava_ctx* ctx, int32_t lb, int32_t lc) {
+  return lb >= 0 && lc > 0 && (int64_t)lb + lc <= ctx->d.L;
+}
+
+}  // namespace
+
+extern "C" int baklava_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host) {
+  if (!shape_ok(desc) || !cap_host) return 0;
+  const int64_t n_caches = (int64_t)desc->L * desc->batch * desc->Hkv;
+  for (int64_t c = 0; c < n_caches; ++c)
+    if (cap_host[c] < 0) return 0;
+  return plan_workspace(desc, cap_host).total;
+}
+
+extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host, const int32_t* cap_host,
+                              const int32_t* len_host, const int32_t* budget_host, baklava_ctx** out) {
+  if (!out) return BAKLAVA_EINVAL;
+  *out = nullptr;
+  if (!shape_ok(desc) || !off_host || !cap_host || !budget_host) return BAKLAVA_EINVAL;
+  if (!desc->k || !desc->v || !desc->score || !desc->pos || !desc->off || !desc->cap || !desc->len ||
+      !desc->budget || !desc->workspace)
+    return BAKLAVA_EINVAL;
+  if (((uintptr_t)desc->k | (uintptr_t)desc->v) & 15) return BAKLAVA_EINVAL;
+  if ((uintptr_t)desc->workspace & 255) return BAKLAVA_EINVAL;
+  const int64_t n_caches = (int64_t)desc->L * desc->batch * desc->Hkv;
+  const int64_t m = (int64_t)desc->L * desc->Hkv;
+  for (int64_t i = 0; i < m; ++i) {
+    if (budget_host[i] < 0) return BAKLAVA_EINVAL;
+    const int need = desc->policy == BAKLAVA_POLICY_SCORE ? desc->sink + desc->recent : desc->sink;
+    if (budget_host[i] < need) return BAKLAVA_EINFEASIBLE;
+  }
+  for (int64_t c = 0; c < n_caches; ++c) {
+    if (cap_host[c] < 0 || off_host[c] < 0) return BAKLAVA_EINVAL;
+    if (len_host && (len_host[c] < 0 || len_host[c] > cap_host[c])) return BAKLAVA_ECAPACITY;
+  }
+  baklava_ctx* ctx = new (std::nothrow) baklava_ctx();
+  if (!ctx) return BAKLAVA_EINVAL;
+  ctx->d = *desc;
+  ctx->n_caches = n_caches;
+  ctx->cpl = desc->batch * desc->Hkv;
+  ctx->G = desc->Hq / desc->Hkv;
+  ctx->row_bytes = desc->D * (desc->dtype == BAKLAVA_BF16 ? 2 : 4);
+  ctx->off.assign(off_host, off_host + n_caches);
+  ctx->cap.assign(cap_host, cap_host + n_caches);
+  if (len_host) ctx->len.assign(len_host, len_host + n_caches);
+  else ctx->len.assign(n_caches, 0);
+  ctx->budget.assign(budget_host, budget_host + m);
+  ctx->kernel_pref = 0;
+  ctx->plan = plan_workspace(desc, cap_host);
+  ctx->ws = reinterpret_cast<char*>(desc->workspace);
+  if (desc->workspace_bytes < ctx->plan.total) { delete ctx; return BAKLAVA_ECAPACITY; }
+
+  int st = build_schedule(ctx, kDefaultChunk);
+  if (st != BAKLAVA_OK) { delete ctx; return st; }
+
+  // Launch orders for eviction: longest caches first, over the whole model and within each layer.
+  std::vector<int32_t> order(n_caches);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return ctx->cap[a] > ctx->cap[b]; });
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_all, order.data(), n_caches * 4, hipMemcpyHostToDevice))) {
+    delete ctx; return BAKLAVA_EHIP;
+  }
+  std::iota(order.begin(), order.end(), 0);
+  for (int32_t l = 0; l < desc->L; ++l)
+    std::stable_sort(order.begin() + (int64_t)l * ctx->cpl, order.begin() + (int64_t)(l + 1) * ctx->cpl,
+                     [&](int32_t a, int32_t b) { return ctx->cap[a] > ctx->cap[b]; });
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_layer, order.data(), n_caches * 4, hipMemcpyHostToDevice))) {
+    delete ctx; return BAKLAVA_EHIP;
+  }
+  *out = ctx;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_destroy(baklava_ctx* ctx) {
+  if (!ctx) return BAKLAVA_EINVAL;
+  delete ctx;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value) {
+  if (!ctx) return BAKLAVA_EINVAL;
+  switch (option) {
+    case BAKLAVA_OPT_CHUNK_TOKENS:
+      if (value < kMinChunk || value % 64 || value > (int64_t)1 << 24) return BAKLAVA_EINVAL;
+      if ((int32_t)value == ctx->chunk) return BAKLAVA_OK;
+      return build_schedule(ctx, (int32_t)value);
+    case BAKLAVA_OPT_KERNEL:
+      if (value < 0 || value > 2) return BAKLAVA_EINVAL;
+      if (value == 2 && !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_EINVAL;
+      if (value == 1 && ctx->G > 8) return BAKLAVA_EINVAL;
+      ctx->kernel_pref = (int32_t)value;
+      return BAKLAVA_OK;
+    default:
+      return BAKLAVA_EINVAL;
+  }
+}
+
+extern "C" int baklava_reset(baklava_ctx* ctx, void* stream) {
+  if (!ctx) return BAKLAVA_EINVAL;
+  if (!hip_ok(launch_fill_i32(ctx->d.len, 0, ctx->n_caches, (hipStream_t)stream))) return BAKLAVA_EHIP;
+  std::fill(ctx->len.begin(), ctx->len.end(), 0);
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_set_lengths(baklava_ctx* ctx, const int32_t* len_host, void* stream) {
+  if (!ctx || !len_host) return BAKLAVA_EINVAL;
+  for (int64_t c = 0; c < ctx->n_caches; ++c) {
+    if (len_host[c] < 0) return BAKLAVA_EINVAL;
+    if (len_host[c] > ctx->cap[c]) return BAKLAVA_ECAPACITY;
+  }
+  ctx->len.assign(len_host, len_host + ctx->n_caches);
+  // The mirror is the staging buffer: wait for the copy so that later appends may change it.
+  if (!hip_ok(hipMemcpyAsync(ctx->d.len, ctx->len.data(), ctx->n_caches * 4, hipMemcpyHostToDevice,
+                             (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
+  if (!hip_ok(hipStreamSynchronize((hipStream_t)stream))) return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_append(baklava_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
+                              int32_t token_pos, void* stream) {
+  if (!ctx || !k_new || !v_new || layer < 0 || layer >= ctx->d.L) return BAKLAVA_EINVAL;
+  if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return BAKLAVA_EINVAL;
+  const int64_t c0 = (int64_t)layer * ctx->cpl;
+  for (int64_t c = c0; c < c0 + ctx->cpl; ++c)
+    if (ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
+  AppendParams p;
+  p.k = ctx->d.k; p.v = ctx->d.v; p.score = ctx->d.score; p.pos = ctx->d.pos;
+  p.off = ctx->d.off; p.cap = ctx->d.cap; p.len = ctx->d.len;
+  p.k_new = k_new; p.v_new = v_new;
+  p.cache_begin = (int32_t)c0; p.token_pos = token_pos; p.row_bytes = ctx->row_bytes;
+  if (!hip_ok(launch_append(p, ctx->cpl, (hipStream_t)stream))) return BAKLAVA_EHIP;
+  for (int64_t c = c0; c < c0 + ctx->cpl; ++c) ctx->len[c] += 1;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                                   const void* q, float* out, void* stream) {
+  if (!ctx || !q || !out || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
+  if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return BAKLAVA_EINVAL;
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  for (int64_t c = c0; c < c1; ++c)
+    if (ctx->len[c] <= 0) return BAKLAVA_ESTATE;
+  const int32_t i0 = ctx->cib[c0], i1 = ctx->cib[c1];
+  DecodeParams p;
+  p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
+  p.off = ctx->d.off; p.len = ctx->d.len;
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items) + i0;
+  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib);
+  p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
+  p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
+  p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
+  p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
+  p.score = ctx->d.score;
+  p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
+  p.cache_begin = (int32_t)c0;
+  p.track = ctx->d.track_scores ? 1 : 0;
+  p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
+  hipStream_t s = (hipStream_t)stream;
+  const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
+  const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
+  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, s)
+                          : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
+  if (!hip_ok(e)) return BAKLAVA_EHIP;
+  if (!hip_ok(launch_combine(p, ctx->d.D, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
+  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, s))) return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                               int32_t* kept_idx_out, void* stream) {
+  if (!ctx || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  CompactParams p;
+  p.k = ctx->d.k; p.v = ctx->d.v; p.score = ctx->d.score; p.pos = ctx->d.pos;
+  p.off = ctx->d.off; p.len = ctx->d.len; p.budget = ctx->d.budget;
+  const bool whole = layer_begin == 0 && layer_count == ctx->d.L;
+  p.order = whole ? reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.order_all)
+                  : reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.order_layer) + c0;
+  p.kept = kept_idx_out ? kept_idx_out : reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.kept);
+  p.info = reinterpret_cast<CompactInfo*>(ctx->ws + ctx->plan.info);
+  p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
+  p.sink = ctx->d.sink; p.recent = ctx->d.recent; p.policy = ctx->d.policy;
+  p.row_bytes = ctx->row_bytes;
+  p.write_identity = kept_idx_out ? 1 : 0;
+  hipStream_t s = (hipStream_t)stream;
+  if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
+  if (!hip_ok(launch_compact_move(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
+  for (int64_t c = c0; c < c1; ++c) {
+    const int32_t b = ctx->budget[(c / ctx->cpl) * ctx->d.Hkv + c % ctx->d.Hkv];
+    ctx->len[c] = std::min(ctx->len[c], b);
+  }
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out) {
+  if (!ctx || !len_host_out) return BAKLAVA_EINVAL;
+  std::memcpy(len_host_out, ctx->len.data(), ctx->n_caches * sizeof(int32_t));
+  return BAKLAVA_OK;
+}

@@ -1,0 +1,87 @@
+// Internal declarations shared by the library's own translation units.
+#ifndef BAKLAVA_COMMON_H
+#define BAKLAVA_COMMON_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace baklava {
+
+// One split-K work item: rows [start, start + count) of cache c; its partial result goes to
+// partial slot `slot`.  Rows at or beyond the cache's live length are skipped by the kernel.
+struct Item {
+  int32_t c, start, count, slot;
+};
+
+// Result of the selection pass for one cache.
+struct CompactInfo {
+  int32_t new_len;      // rows that survive
+  int32_t first_moved;  // smallest evicted row index (== old length when nothing is evicted)
+  int32_t old_len;
+  int32_t pad;
+};
+
+struct DecodeParams {
+  const void* k;
+  const void* v;
+  const void* q;
+  float* out;
+  const int64_t* off;
+  const int32_t* len;
+  const Item* items;               // first item of the launched range
+  const int32_t* cache_item_begin; // [n_caches + 1], absolute item index
+  float* part_o;                   // [n_items, G, D] un-normalised partial outputs
+  float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
+  float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
+  float* logits;                   // [total_tokens, G] scaled logits in log2 units (track_scores)
+  float* score;
+  int32_t G, Hq, Hkv, batch;
+  int32_t cache_begin;             // first cache id of the launched range
+  int32_t track;
+  float scale_log2e;               // log2(e) / sqrt(D)
+};
+
+struct AppendParams {
+  void* k;
+  void* v;
+  float* score;
+  int32_t* pos;
+  const int64_t* off;
+  const int32_t* cap;
+  int32_t* len;
+  const void* k_new;
+  const void* v_new;
+  int32_t cache_begin;
+  int32_t token_pos;
+  int32_t row_bytes;
+};
+
+struct CompactParams {
+  void* k;
+  void* v;
+  float* score;
+  int32_t* pos;
+  const int64_t* off;
+  int32_t* len;
+  const int32_t* budget;
+  const int32_t* order;  // launch order: blockIdx.x -> cache id
+  int32_t* kept;         // [total_tokens], packed by off
+  CompactInfo* info;     // [n_caches]
+  int32_t Hkv, batch;
+  int32_t sink, recent, policy;
+  int32_t row_bytes;
+  int32_t write_identity;  // 1: also write 0..n-1 for caches that evict nothing
+};
+
+// Launchers (defined next to their kernels).  All return hipError_t of the launch.
+hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s);
+hipError_t launch_combine(const DecodeParams& p, int D, int n_caches, hipStream_t s);
+hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s);
+hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
+hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
+hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s);
+hipError_t launch_compact_move(const CompactParams& p, int n_caches, hipStream_t s);
+
+}  // namespace baklava
+#endif

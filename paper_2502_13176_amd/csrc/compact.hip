@@ -1,0 +1,203 @@
+// Budget-enforcing eviction (f_evict, Eqs. 5-6): selection of the surviving rows, then a stable
+// in-place move.  One workgroup per cache; long caches are launched first.
+#include "common.h"
+
+namespace baklava {
+
+namespace {
+
+constexpr int kSelThreads = 512;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Order-preserving map from fp32 to uint32 (larger float -> larger key); -0 is folded onto +0 so
+// that it ties with it, as a floating-point comparison would.
+__device__ __forceinline__ uint32_t score_key(float f) {
+  const uint32_t u = __float_as_uint(f + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of `v` over the workgroup; `total` receives the sum.  `sm` holds one
+// word per wavefront.  Ends with a barrier, so `sm` can be reused right away.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* sm, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) sm[wave] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int x = sm[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  total = tot;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactParams p) {
+  const int c = p.order[blockIdx.x];
+  const int tid = threadIdx.x;
+  const int n = p.len[c];
+  const int cpl = p.batch * p.Hkv;
+  const int b = p.budget[(c / cpl) * p.Hkv + c % p.Hkv];
+  const int64_t off = p.off[c];
+  int32_t* kept = p.kept + off;
+  const float* score = p.score + off;
+
+  if (n <= b) {
+    if (p.write_identity)
+      for (int j = tid; j < n; j += kSelThreads) kept[j] = j;
+    if (tid == 0) p.info[c] = CompactInfo{n, n, n, 0};
+    return;
+  }
+  const int s = p.sink;
+  const int r = (p.policy == 1) ? (b - s) : p.recent;
+  const int k = b - s - r;  // middle rows that survive, >= 0 (checked at context creation)
+  const int mid_lo = s, mid_hi = n - r;
+
+  __shared__ int hist[256];
+  __shared__ int sm_scan[kSelWaves];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_need, sh_first;
+
+  uint32_t thr = 0;
+  int need_eq = 0;
+  if (k > 0) {
+    // Radix select of the k-th largest key of the middle, 8 bits per pass, high digits first.
+    uint32_t prefix = 0, mask = 0;
+    int need = k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
+      __syncthreads();
+      for (int j = mid_lo + tid; j < mid_hi; j += kSelThreads) {
+        const uint32_t key = score_key(score[j]);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int cum = 0, d = 255;
+        for (; d > 0; --d) {
+          if (cum + hist[d] >= need) break;
+          cum += hist[d];
+        }
+        sh_prefix = prefix | ((uint32_t)d << shift);
+        sh_need = need - cum;
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      need = sh_need;
+      mask |= 0xffu << shift;
+      __syncthreads();
+    }
+    thr = prefix;
+    need_eq = need;  // rows whose key equals thr that still survive (oldest first)
+  }
+
+  if (tid == 0) sh_first = n;
+  __syncthreads();
+  int eq_base = 0, out_base = 0;
+  for (int j0 = 0; j0 < n; j0 += kSelThreads) {
+    const int j = j0 + tid;
+    const bool in = j < n;
+    const bool fixed = in && (j < mid_lo || j >= mid_hi);
+    uint32_t key = 0;
+    const bool middle = in && !fixed;
+    if (middle && k > 0) key = score_key(score[j]);
+    const int is_eq = (middle && k > 0 && key == thr) ? 1 : 0;
+    int eq_total;
+    const int eq_rank = eq_base + block_exclusive_scan(is_eq, sm_scan, eq_total);
+    eq_base += eq_total;
+    const bool keep = fixed || (middle && k > 0 && (key > thr || (is_eq && eq_rank < need_eq)));
+    int keep_total;
+    const int dst = out_base + block_exclusive_scan(keep ? 1 : 0, sm_scan, keep_total);
+    out_base += keep_total;
+    if (keep) kept[dst] = j;
+    else if (in) atomicMin(&sh_first, j);
+  }
+  __syncthreads();
+  if (tid == 0) p.info[c] = CompactInfo{b, sh_first, n, 0};
+}
+
+constexpr int kMoveThreads = 512;
+constexpr int kMoveRows = 128;  // rows per tile
+
+// Row p <- row kept[p], p ascending.  kept[p] >= p, so a tile's sources are never rows an
+// earlier tile wrote, and within a tile every load finishes (barrier) before any store.
+template <int PIECES>  // 16-byte pieces per row
+__global__ __launch_bounds__(kMoveThreads) void compact_move_kernel(CompactParams p) {
+  const int c = p.order[blockIdx.x];
+  const CompactInfo info = p.info[c];
+  if (info.first_moved >= info.old_len) return;  // nothing evicted
+  const int tid = threadIdx.x;
+  const int64_t off = p.off[c];
+  const int32_t* kept = p.kept + off;
+  const int b = info.new_len;
+  constexpr int PER_PLANE = kMoveRows * PIECES / kMoveThreads;  // pieces per thread per plane
+  uint4* K = reinterpret_cast<uint4*>(p.k) + off * PIECES;
+  uint4* V = reinterpret_cast<uint4*>(p.v) + off * PIECES;
+  float* score = p.score + off;
+  int32_t* pos = p.pos + off;
+
+  const int first = (info.first_moved / kMoveRows) * kMoveRows;
+  for (int p0 = first; p0 < b; p0 += kMoveRows) {
+    uint4 kb[PER_PLANE], vb[PER_PLANE];
+    float sc = 0.f;
+    int ps = 0;
+#pragma unroll
+    for (int i = 0; i < PER_PLANE; ++i) {
+      const int idx = tid + i * kMoveThreads;
+      const int row = min(p0 + idx / PIECES, b - 1), piece = idx % PIECES;  // clamped: a live row
+      const int64_t src = kept[row];
+      kb[i] = K[src * PIECES + piece];
+      vb[i] = V[src * PIECES + piece];
+    }
+    if (tid < kMoveRows && p0 + tid < b) {
+      const int src = kept[p0 + tid];
+      sc = score[src];
+      ps = pos[src];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PER_PLANE; ++i) {
+      const int idx = tid + i * kMoveThreads;
+      const int row = p0 + idx / PIECES, piece = idx % PIECES;
+      if (row < b) {
+        K[(int64_t)row * PIECES + piece] = kb[i];
+        V[(int64_t)row * PIECES + piece] = vb[i];
+      }
+    }
+    if (tid < kMoveRows && p0 + tid < b) {
+      score[p0 + tid] = sc;
+      pos[p0 + tid] = ps;
+    }
+  }
+  if (tid == 0) p.len[c] = b;
+}
+
+}  // namespace
+
+hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s) {
+  if (n_caches <= 0) return hipSuccess;
+  compact_select_kernel<<<dim3(n_caches), dim3(kSelThreads), 0, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_move(const CompactParams& p, int n_caches, hipStream_t s) {
+  if (n_caches <= 0) return hipSuccess;
+  const dim3 grid(n_caches), block(kMoveThreads);
+  switch (p.row_bytes / 16) {
+    case 8: compact_move_kernel<8><<<grid, block, 0, s>>>(p); break;
+    case 16: compact_move_kernel<16><<<grid, block, 0, s>>>(p); break;
+    case 32: compact_move_kernel<32><<<grid, block, 0, s>>>(p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace baklava

@@ -1,0 +1,332 @@
+// Decode attention over ragged caches, vector-ALU version, plus the kernels every decode call
+// shares: split combine, score update, append, fill.
+//
+// Each work item (a run of rows of one cache) is one workgroup of four wavefronts.  A 256-byte
+// row is spread over 16 lanes as 16-byte pieces, so one wavefront load instruction fetches four
+// whole rows, fully coalesced.  Each lane group keeps its own running (max, sum, output) for
+// every query head of the group (online softmax, Eq. 1 re-associated) and the groups are merged
+// once at the end: no barrier and no cross-group traffic inside the streaming loop.
+#include "common.h"
+
+namespace baklava {
+
+namespace {
+
+struct bf16x8 { uint4 raw; };
+
+template <typename T> struct Row;
+template <> struct Row<float> {
+  static constexpr int EPL = 4;  // elements per 16-byte piece
+  __device__ static void widen(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+template <> struct Row<uint16_t> {  // bf16 storage
+  static constexpr int EPL = 8;
+  __device__ static void widen(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+// Merge two online-softmax states that share a query head.
+__device__ __forceinline__ void merge_state(float& m, float& l, float* acc, int n_acc, float mo,
+                                            float lo, const float* acco) {
+  const float mn = fmaxf(m, mo);
+  const float ms = (mn == kNegInf) ? 0.f : mn;
+  const float a = fast_exp2(m - ms), b = fast_exp2(mo - ms);
+  l = l * a + lo * b;
+  for (int e = 0; e < n_acc; ++e) acc[e] = acc[e] * a + acco[e] * b;
+  m = mn;
+}
+
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
+  constexpr int EPL = Row<T>::EPL;
+  constexpr int LPR = D / EPL;   // lanes per row
+  constexpr int RPW = 64 / LPR;  // rows per wavefront load
+  constexpr int U = 4;           // rows in flight per lane
+  constexpr int TILE = RPW * U;
+  constexpr int NW = 4;
+
+  const Item it = p.items[blockIdx.x];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int G = p.G;
+  const int n = p.len[it.c];
+  int cnt = min(it.start + it.count, n) - it.start;
+  if (cnt < 0) cnt = 0;
+  const int64_t row0 = p.off[it.c] + it.start;
+  const T* Kb = reinterpret_cast<const T*>(p.k) + row0 * D + sub * EPL;
+  const T* Vb = reinterpret_cast<const T*>(p.v) + row0 * D + sub * EPL;
+
+  const int c_rel = it.c - p.cache_begin;
+  const int64_t qrow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
+  float qr[GT][EPL];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    if (g < G) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(p.q) +
+                                                        (qrow0 + g) * D + sub * EPL);
+      Row<T>::widen(raw, qr[g]);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qr[g][e] *= p.scale_log2e;
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qr[g][e] = 0.f;
+    }
+  }
+
+  float m[GT], l[GT], acc[GT][EPL];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    m[g] = kNegInf; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+
+  for (int t0 = wave * TILE; t0 < cnt; t0 += NW * TILE) {
+    uint4 kraw[U], vraw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = min(t0 + u * RPW + rg, cnt - 1);  // clamped: always a live row of this item
+      kraw[u] = *reinterpret_cast<const uint4*>(Kb + (int64_t)r * D);
+      vraw[u] = *reinterpret_cast<const uint4*>(Vb + (int64_t)r * D);
+    }
+    float s[U][GT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Row<T>::widen(kraw[u], kf);
+      const int r = t0 + u * RPW + rg;
+      const bool live = r < cnt;
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) d = fmaf(qr[g][e], kf[e], d);
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o);
+        s[u][g] = live ? d : kNegInf;
+      }
+      if (p.track && live) {
+#pragma unroll
+        for (int g = 0; g < GT; ++g)
+          if (sub == g && g < G) p.logits[(row0 + r) * G + g] = s[u][g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float mx = s[0][g];
+#pragma unroll
+      for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][g]);
+      const float mn = fmaxf(m[g], mx);
+      const float ms = (mn == kNegInf) ? 0.f : mn;
+      const float alpha = fast_exp2(m[g] - ms);
+      m[g] = mn;
+      l[g] *= alpha;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < U; ++u) s[u][g] = fast_exp2(s[u][g] - ms);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float vf[EPL];
+      Row<T>::widen(vraw[u], vf);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        l[g] += s[u][g];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(s[u][g], vf[e], acc[g][e]);
+      }
+    }
+  }
+
+  // Merge the lane groups of a wavefront (lanes with equal `sub`).
+#pragma unroll
+  for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float acco[EPL];
+      const float mo = __shfl_xor(m[g], o), lo = __shfl_xor(l[g], o);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acco[e] = __shfl_xor(acc[g][e], o);
+      merge_state(m[g], l[g], acc[g], EPL, mo, lo, acco);
+    }
+  }
+
+  // Merge the four wavefronts through LDS and write the item's partial.
+  __shared__ float sm_m[NW][GT], sm_l[NW][GT];
+  __shared__ float sm_acc[NW][GT][D];
+  if (rg == 0) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      if (sub == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sm_acc[wave][g][sub * EPL + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int g = idx / D, d = idx % D;
+    float mm = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, sm_m[w][g]);
+    const float ms = (mm == kNegInf) ? 0.f : mm;
+    float ll = 0.f, oo = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float a = fast_exp2(sm_m[w][g] - ms);
+      ll += sm_l[w][g] * a;
+      oo += sm_acc[w][g][d] * a;
+    }
+    p.part_o[((int64_t)it.slot * G + g) * D + d] = oo;
+    if (d == 0) {
+      p.part_ml[((int64_t)it.slot * G + g) * 2 + 0] = mm;
+      p.part_ml[((int64_t)it.slot * G + g) * 2 + 1] = ll;
+    }
+  }
+}
+
+// out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M): the same softmax as Eq. 7, with the sum
+// over rows regrouped by split.  One wavefront per (cache, query head).
+template <int D>
+__global__ __launch_bounds__(64) void combine_kernel(DecodeParams p) {
+  const int G = p.G;
+  const int c = p.cache_begin + blockIdx.x / G;
+  const int g = blockIdx.x % G;
+  const int lane = threadIdx.x;
+  const int ib = p.cache_item_begin[c], ie = p.cache_item_begin[c + 1];
+  float M = kNegInf;
+  for (int s = ib + lane; s < ie; s += 64) M = fmaxf(M, p.part_ml[((int64_t)s * G + g) * 2]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  const float Ms = (M == kNegInf) ? 0.f : M;
+  constexpr int PER = D / 64;
+  float o[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) o[i] = 0.f;
+  float Lsum = 0.f;
+  for (int s = ib; s < ie; ++s) {
+    const float ms = p.part_ml[((int64_t)s * G + g) * 2];
+    const float ls = p.part_ml[((int64_t)s * G + g) * 2 + 1];
+    const float a = fast_exp2(ms - Ms);
+    Lsum += ls * a;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) o[i] += p.part_o[((int64_t)s * G + g) * D + lane + 64 * i] * a;
+  }
+  const float inv = 1.f / Lsum;
+  const int c_rel = c - p.cache_begin;
+  const int64_t orow = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G + g;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) p.out[orow * D + lane + 64 * i] = o[i] * inv;
+  if (lane == 0) {
+    p.final_ml[((int64_t)c * G + g) * 2 + 0] = Ms;
+    p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
+  }
+}
+
+// score_j += sum_g 2^(s_gj - M_g) / L_g  (cumulative attention per cached token, summed over the
+// query heads that share the cache).
+__global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
+  const Item it = p.items[blockIdx.x];
+  const int G = p.G;
+  const int n = p.len[it.c];
+  const int cnt = min(it.start + it.count, n) - it.start;
+  const int64_t row0 = p.off[it.c] + it.start;
+  for (int r = threadIdx.x; r < cnt; r += 256) {
+    float w = 0.f;
+    for (int g = 0; g < G; ++g) {
+      const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
+      const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
+      w += fast_exp2(p.logits[(row0 + r) * G + g] - M) * inv;
+    }
+    p.score[row0 + r] += w;
+  }
+}
+
+// [K'; K_t], [V'; V_t] of Eq. 7: the new row goes to slot len, then len += 1.
+__global__ __launch_bounds__(64) void append_kernel(AppendParams p) {
+  const int c = p.cache_begin + blockIdx.x;
+  const int n = p.len[c];
+  if (n >= p.cap[c]) return;  // the host has already refused this case
+  const int64_t row = p.off[c] + n;
+  const int pieces = p.row_bytes / 16;
+  const int lane = threadIdx.x;
+  const int plane = lane / 32, piece = lane % 32;
+  if (piece < pieces) {
+    const char* src = reinterpret_cast<const char*>(plane ? p.v_new : p.k_new) +
+                      (int64_t)blockIdx.x * p.row_bytes + piece * 16;
+    char* dst = reinterpret_cast<char*>(plane ? p.v : p.k) + row * p.row_bytes + piece * 16;
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  }
+  if (lane == 63) {
+    p.score[row] = 0.f;
+    p.pos[row] = p.token_pos;
+  }
+  __syncthreads();
+  if (lane == 0) p.len[c] = n + 1;
+}
+
+__global__ void fill_i32_kernel(int32_t* dst, int32_t value, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+
+template <typename T, int D>
+hipError_t launch_valu_g(const DecodeParams& p, int n_items, hipStream_t s) {
+  const dim3 grid(n_items), block(256);
+  if (p.G <= 2) decode_partial_valu<T, D, 2><<<grid, block, 0, s>>>(p);
+  else if (p.G <= 4) decode_partial_valu<T, D, 4><<<grid, block, 0, s>>>(p);
+  else if (p.G <= 8) decode_partial_valu<T, D, 8><<<grid, block, 0, s>>>(p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  if (dtype == 0 && D == 128) return launch_valu_g<uint16_t, 128>(p, n_items, s);
+  if (dtype == 0 && D == 64) return launch_valu_g<uint16_t, 64>(p, n_items, s);
+  if (dtype == 1 && D == 128) return launch_valu_g<float, 128>(p, n_items, s);
+  if (dtype == 1 && D == 64) return launch_valu_g<float, 64>(p, n_items, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_combine(const DecodeParams& p, int D, int n_caches, hipStream_t s) {
+  if (n_caches <= 0) return hipSuccess;
+  const dim3 grid(n_caches * p.G), block(64);
+  if (D == 128) combine_kernel<128><<<grid, block, 0, s>>>(p);
+  else if (D == 64) combine_kernel<64><<<grid, block, 0, s>>>(p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  score_update_kernel<<<dim3(n_items), dim3(256), 0, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s) {
+  if (n_caches <= 0) return hipSuccess;
+  append_kernel<<<dim3(n_caches), dim3(64), 0, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(dst, value, n);
+  return hipGetLastError();
+}
+
+}  // namespace baklava

@@ -1,0 +1,149 @@
+// Host-only part of libbaklava: budget allocation and arena layout.
+// No GPU call is made from this file.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <numeric>
+#include <vector>
+
+#include "baklava.h"
+
+namespace {
+
+typedef unsigned __int128 u128;
+constexpr int kFracBits = 40;
+constexpr uint64_t kOne = uint64_t(1) << kFracBits;
+
+inline int64_t clip64(u128 x, int64_t lo, int64_t hi) {
+  if (x < (u128)lo) return lo;
+  if (x > (u128)hi) return hi;
+  return (int64_t)x;
+}
+
+}  // namespace
+
+extern "C" const char* baklava_strerror(int status) {
+  switch (status) {
+    case BAKLAVA_OK: return "ok";
+    case BAKLAVA_EINVAL: return "invalid argument";
+    case BAKLAVA_EINFEASIBLE: return "budget constraints cannot be met";
+    case BAKLAVA_ECAPACITY: return "capacity exceeded";
+    case BAKLAVA_EHIP: return "HIP runtime call failed";
+    case BAKLAVA_ESTATE: return "call order violated";
+    default: return "unknown status";
+  }
+}
+
+// Proportional budgets with an exact sum (Methods, "Assigning Memory Budgets to KV-Caches").
+// Fixed-point weights make every rounding an integer decision.
+extern "C" int baklava_alloc_proportional(const double* importance, int32_t m, int64_t global_budget,
+                                          int32_t lo, int32_t hi, int32_t* budget_out) {
+  if (!importance || !budget_out || m <= 0 || lo < 0 || hi < lo || global_budget < 0) return BAKLAVA_EINVAL;
+  double top = 0.0;
+  for (int32_t i = 0; i < m; ++i) {
+    const double v = importance[i];
+    if (!std::isfinite(v) || !(v > 0.0)) return BAKLAVA_EINVAL;
+    top = std::max(top, v);
+  }
+  if ((int64_t)m * lo > global_budget || (int64_t)m * hi < global_budget) return BAKLAVA_EINFEASIBLE;
+
+  std::vector<uint64_t> w(m);
+  uint64_t wmin = kOne;
+  for (int32_t i = 0; i < m; ++i) {
+    const double scaled = std::floor((importance[i] / top) * (double)kOne);
+    w[i] = scaled < 1.0 ? 1 : (uint64_t)scaled;
+    wmin = std::min(wmin, w[i]);
+  }
+  auto filled = [&](u128 lam) -> int64_t {
+    int64_t s = 0;
+    for (int32_t i = 0; i < m; ++i) s += clip64((lam * w[i]) >> kFracBits, lo, hi);
+    return s;
+  };
+  // Above lam_top every head is clipped to hi.
+  const u128 lam_top = (((u128)hi << kFracBits) / wmin) + 1;
+  u128 lam;
+  if (filled(lam_top) <= global_budget) {
+    lam = lam_top;
+  } else {
+    u128 a = 0, z = lam_top;  // filled(a) <= B < filled(z)
+    while (z - a > 1) {
+      const u128 mid = a + (z - a) / 2;
+      if (filled(mid) <= global_budget) a = mid; else z = mid;
+    }
+    lam = a;
+  }
+  struct Cand { uint64_t frac, w; int32_t i; };
+  std::vector<Cand> elig;
+  int64_t sum = 0;
+  for (int32_t i = 0; i < m; ++i) {
+    const u128 prod = lam * w[i];
+    const u128 x = prod >> kFracBits;
+    const int64_t b = clip64(x, lo, hi);
+    budget_out[i] = (int32_t)b;
+    sum += b;
+    if (x >= (u128)lo && x < (u128)hi) elig.push_back({(uint64_t)(prod & (kOne - 1)), w[i], i});
+  }
+  int64_t left = global_budget - sum;
+  if (left < 0 || left > (int64_t)elig.size()) return BAKLAVA_EINFEASIBLE;  // cannot happen
+  std::sort(elig.begin(), elig.end(), [](const Cand& p, const Cand& q) {
+    if (p.frac != q.frac) return p.frac > q.frac;
+    if (p.w != q.w) return p.w > q.w;
+    return p.i < q.i;
+  });
+  for (int64_t r = 0; r < left; ++r) budget_out[elig[r].i] += 1;
+  return BAKLAVA_OK;
+}
+
+// Algorithm 2: shrink the caches below the importance threshold, hand what they free to the
+// most important of the others.
+extern "C" int baklava_alloc_threshold(const double* importance, int32_t m, const int32_t* size_in,
+                                       double t, double r, int32_t* budget_out) {
+  if (!importance || !size_in || !budget_out || m <= 0) return BAKLAVA_EINVAL;
+  if (!(r >= 0.0 && r <= 1.0)) return BAKLAVA_EINVAL;
+  std::vector<int64_t> size(m);
+  std::vector<int32_t> low, high;
+  for (int32_t i = 0; i < m; ++i) {
+    if (size_in[i] < 0) return BAKLAVA_EINVAL;
+    size[i] = size_in[i];
+    (importance[i] < t ? low : high).push_back(i);
+  }
+  const int64_t n = (int64_t)low.size();
+  if (n != 0 && n != m) {
+    int64_t freed = 0;
+    for (int32_t i : low) {
+      const int64_t d = (int64_t)std::floor(r * (double)size[i]);
+      size[i] -= d;
+      freed += d;
+    }
+    const int64_t k = std::min<int64_t>(n, m - n);
+    std::stable_sort(high.begin(), high.end(),
+                     [&](int32_t a, int32_t b) { return importance[a] > importance[b]; });
+    const int64_t base = freed / k, rem = freed % k;
+    for (int64_t rank = 0; rank < k; ++rank) size[high[rank]] += base + (rank < rem ? 1 : 0);
+  }
+  for (int32_t i = 0; i < m; ++i) {
+    if (size[i] > INT32_MAX) return BAKLAVA_EINVAL;
+    budget_out[i] = (int32_t)size[i];
+  }
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int32_t batch,
+                              int32_t slack, int64_t* off_out, int32_t* cap_out,
+                              int64_t* total_tokens_out) {
+  if (!budget || !off_out || !cap_out || !total_tokens_out) return BAKLAVA_EINVAL;
+  if (L <= 0 || Hkv <= 0 || batch <= 0 || slack < 0) return BAKLAVA_EINVAL;
+  int64_t total = 0;
+  for (int32_t l = 0; l < L; ++l)
+    for (int32_t b = 0; b < batch; ++b)
+      for (int32_t h = 0; h < Hkv; ++h) {
+        const int64_t bud = budget[(int64_t)l * Hkv + h];
+        if (bud < 0 || bud + slack > INT32_MAX) return BAKLAVA_EINVAL;
+        const int64_t c = ((int64_t)l * batch + b) * Hkv + h;
+        off_out[c] = total;
+        cap_out[c] = (int32_t)(bud + slack);
+        total += bud + slack;
+      }
+  *total_tokens_out = total;
+  return BAKLAVA_OK;
+}

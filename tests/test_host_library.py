@@ -1,0 +1,105 @@
+"""CPU-side checks of libbaklava: it loads, exports what the header declares, and its host
+allocators agree bit-for-bit with the oracle and with the stored budgets."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import baklava_oracle as O
+from paper_2502_13176_amd import binding as B
+from paper_2502_13176_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "baklava.h")).read()
+    declared = set(re.findall(r"\b(baklava_[a-z_]+)\s*\(", header))
+    declared -= {"baklava_ctx", "baklava_desc"}
+    assert declared == set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror():
+    assert B.strerror(B.OK) == "ok"
+    assert "capacity" in B.strerror(B.ECAPACITY)
+    assert B.strerror(99) == "unknown status"
+
+
+@pytest.mark.parametrize("name", ["llama1", "llama32", "qwen", "long"])
+def test_proportional_budgets_match_oracle_and_golden(name):
+    w = synth.WORKLOADS[name]
+    mine = synth.budgets_for(w, B.alloc_proportional)
+    assert mine == synth.budgets_for(w, O.alloc_proportional)
+    golden = [int(x) for x in open(os.path.join(ROOT, "tests", "golden", f"budgets_{name}.txt"))
+              if not x.startswith("#")]
+    assert mine == golden
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_proportional_random_vs_oracle(seed):
+    rng = np.random.default_rng(seed)
+    m = int(rng.integers(1, 300))
+    imp = rng.lognormal(0, 2.0, m) if seed % 2 else 1 + rng.pareto(1.1, m)
+    if seed % 5 == 0:
+        imp = np.round(imp, 1) + 0.1          # many exact ties
+    lo = int(rng.integers(0, 200))
+    hi = lo + int(rng.integers(0, 100000))
+    Bt = int(rng.integers(m * lo, m * hi + 1))
+    assert B.alloc_proportional(imp, Bt, lo, hi) == O.alloc_proportional(imp, Bt, lo, hi)
+
+
+def test_proportional_error_codes():
+    def status(imp, Bt, lo, hi):
+        with pytest.raises(B.BaklavaError) as e:
+            B.alloc_proportional(imp, Bt, lo, hi)
+        return e.value.status
+    assert status([1.0, 1.0], 5, 3, 10) == B.EINFEASIBLE
+    assert status([1.0, 1.0], 25, 3, 10) == B.EINFEASIBLE
+    assert status([1.0, 0.0], 10, 3, 10) == B.EINVAL
+    assert status([1.0, float("inf")], 10, 3, 10) == B.EINVAL
+    assert status([1.0, 1.0], 10, 5, 3) == B.EINVAL
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_threshold_random_vs_oracle(seed):
+    rng = np.random.default_rng(1000 + seed)
+    m = int(rng.integers(1, 200))
+    imp = np.round(rng.random(m), 2) if seed % 3 == 0 else rng.random(m)
+    size = rng.integers(0, 40000, m)
+    t, r = float(rng.random()), float(rng.random())
+    assert B.alloc_threshold(imp, size, t, r) == O.alloc_threshold(imp, size, t, r)
+
+
+def test_threshold_error_codes():
+    with pytest.raises(B.BaklavaError) as e:
+        B.alloc_threshold([0.1, 0.9], [10, 10], 0.5, 1.5)
+    assert e.value.status == B.EINVAL
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama1", "qwen"])
+def test_layout_matches_oracle(name):
+    w = synth.WORKLOADS[name]
+    b = synth.budgets_for(w, O.alloc_proportional)
+    off, cap, total = B.layout(b, w.L, w.Hkv, w.batch, w.slack)
+    ooff, ocap, ototal = O.layout(b, w.L, w.Hkv, w.batch, w.slack)
+    assert off.tolist() == ooff and cap.tolist() == ocap and total == ototal
+
+
+def test_workspace_bytes_is_a_pure_host_query():
+    w = synth.WORKLOADS["llama1"]
+    b = synth.budgets_for(w, B.alloc_proportional)
+    _, cap, total = B.layout(b, w.L, w.Hkv, w.batch, w.slack)
+    d = B.Desc()
+    d.L, d.Hq, d.Hkv, d.D, d.batch, d.dtype = w.L, w.Hq, w.Hkv, w.D, w.batch, B.BF16
+    d.sink, d.recent = w.sink, w.recent
+    n0 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32)))
+    d.track_scores = 1
+    n1 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32)))
+    assert n0 > 0 and n1 == n0 + ((total * w.G * 4 + 255) // 256) * 256
+    d.D = 96
+    assert B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32))) == 0

@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the ragged per-head KV-cache decode path on one MI355X.
+
+One "step" is one decode step of the whole model: for every layer append the new K/V row to each
+cache and run single-query attention over the ragged caches; every `interval` steps evict every
+cache back to its budget.  Inputs are synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is K/V bytes read by attention per second over the timed steps
+(appends and evictions included in the time, not in the bytes).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="llama32", choices=["tiny", "llama1", "llama32", "qwen", "long"])
+    ap.add_argument("--mode", default="layer", choices=["layer", "stack"],
+                    help="layer: one attention launch per layer (as a model would issue them); "
+                         "stack: one launch over all layers")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
+    ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle leg")
+    return ap.parse_args()
+
+
+def fill_arena_on_device(arena, w, torch):
+    """Seeded N(0,1) payload rounded to bf16, generated on the device in slabs."""
+    g = torch.Generator(device=arena.device)
+    g.manual_seed(w.seed)
+    slab = 1 << 22  # rows
+    for plane in (arena.k, arena.v):
+        for r0 in range(0, arena.total_tokens, slab):
+            r1 = min(arena.total_tokens, r0 + slab)
+            x = torch.randn((r1 - r0, w.D), generator=g, device=arena.device, dtype=torch.float32)
+            plane[r0:r1].copy_(x)
+            del x
+    if w.scores == "uniform":
+        arena.score.copy_(torch.rand((arena.total_tokens,), generator=g, device=arena.device, dtype=torch.float32))
+    else:
+        arena.score.zero_()
+    # original positions: 0..n-1 inside each cache
+    off = torch.from_numpy(arena.off_host).to(arena.device)
+    cap = torch.from_numpy(arena.cap_host).to(arena.device).to(torch.int64)
+    starts = torch.repeat_interleave(off, cap)
+    arena.pos.copy_((torch.arange(arena.total_tokens, device=arena.device) - starts).to(torch.int32))
+    return g
+
+
+def cpu_baseline(arena, w, q_dev, torch, target_seconds):
+    """The fp64 oracle's decode attention timed on this machine's host cores over a bounded sample of
+    the same caches (layer 0 first, then further layers until the time target is met)."""
+    import numpy as np
+    from oracle import baklava_oracle as O
+    from paper_2502_13176_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    lens = arena.lengths()
+    q_host = q_dev.view(torch.int16).cpu().numpy().view(np.uint16) if w.dtype == "bf16" else q_dev.cpu().numpy()
+    q64 = synth.storage_to_f64(q_host, w.dtype)
+    cpl = w.batch * w.Hkv
+    t_used, bytes_done, n_done = 0.0, 0, 0
+    for c in range(arena.n_caches):
+        o, n = int(arena.off_host[c]), int(lens[c])
+        if w.dtype == "bf16":
+            Ks = arena.k[o:o + n].view(torch.int16).cpu().numpy().view(np.uint16)
+            Vs = arena.v[o:o + n].view(torch.int16).cpu().numpy().view(np.uint16)
+        else:
+            Ks, Vs = arena.k[o:o + n].cpu().numpy(), arena.v[o:o + n].cpu().numpy()
+        l, rem = divmod(c, cpl)
+        b, h = divmod(rem, w.Hkv)
+        t0 = time.perf_counter()
+        O.decode_attn(q64[l, b, h * w.G:(h + 1) * w.G], synth.storage_to_f64(Ks, w.dtype),
+                      synth.storage_to_f64(Vs, w.dtype))
+        t_used += time.perf_counter() - t0
+        bytes_done += n * w.token_bytes
+        n_done += 1
+        if t_used >= target_seconds:
+            break
+    return {
+        "value": round(bytes_done / t_used / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"fp64 oracle decode attention over the first {n_done} of {arena.n_caches} caches "
+                  f"({bytes_done / 1e6:.1f} MB of K/V, {t_used:.1f} s), widening of the stored rows included",
+    }
+
+
+def read_traffic():
+    """HBM bytes per launch of the dominant kernel, from the committed counter summary (if any)."""
+    path = os.path.join(ROOT, "profiles", "decode_partial_mfma_llama32_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2502_13176_amd import binding as B
+    from paper_2502_13176_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    track = w.scores == "kernel"
+    arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack, w.sink, w.recent,
+                    B.POLICY_SCORE, track)
+    gen = fill_arena_on_device(arena, w, torch)
+    cpl = w.batch * w.Hkv
+    lens0 = np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], dtype=np.int32)
+    lens0 = np.minimum(lens0, w.ctx)
+    arena.set_lengths(lens0)
+    if args.kernel:
+        arena.set_option(B.OPT_KERNEL, args.kernel)
+    if args.chunk:
+        arena.set_option(B.OPT_CHUNK_TOKENS, args.chunk)
+    arena.set_option(B.OPT_TIME_KERNEL, 1)
+
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    q = torch.randn((w.L, w.batch, w.Hq, w.D), generator=gen, device=arena.device, dtype=torch.float32).to(tdt)
+    k_new = torch.randn((w.L, w.batch, w.Hkv, w.D), generator=gen, device=arena.device, dtype=torch.float32).to(tdt)
+    v_new = torch.randn((w.L, w.batch, w.Hkv, w.D), generator=gen, device=arena.device, dtype=torch.float32).to(tdt)
+    out = torch.zeros((w.L, w.batch, w.Hq, w.D), device=arena.device, dtype=torch.float32)
+    torch.cuda.synchronize()
+
+    state = {"t": 0, "kv_bytes": 0, "compactions": 0}
+    interval = 0 if args.no_compaction else w.interval
+
+    def step():
+        state["t"] += 1
+        t = state["t"]
+        if args.mode == "layer":
+            for l in range(w.L):
+                arena.append(l, k_new[l], v_new[l], w.ctx + t)
+                arena.decode_attn(l, 1, q[l], out[l])
+        else:
+            for l in range(w.L):
+                arena.append(l, k_new[l], v_new[l], w.ctx + t)
+            arena.decode_attn(0, w.L, q, out)
+        state["kv_bytes"] += int(arena.lengths().astype(np.int64).sum()) * w.token_bytes
+        if interval and t % interval == 0:
+            arena.compact(0, w.L)
+            state["compactions"] += 1
+        elif not interval and (t % w.slack == 0):
+            # appends only: start again from the budgets before a cache overflows
+            arena.set_lengths(lens0)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    arena.profile_read()                      # discard warm-up kernel timings
+    state["kv_bytes"] = 0
+    state["compactions"] = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, launches = arena.profile_read()
+    arena.set_option(B.OPT_TIME_KERNEL, 0)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    gbps = state["kv_bytes"] / elapsed / 1e9
+    avg_launch_bytes = state["kv_bytes"] / max(1, launches)
+    avg_launch_s = kernel_ms * 1e-3 / max(1, launches)
+    achieved = avg_launch_bytes / avg_launch_s / 1e9 if launches else 0.0
+
+    result = {
+        "metric": "decode-attn KV bytes read/s", "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {w.L} layers x {w.Hkv} KV heads (G={w.G}), D={w.D}, batch {w.batch}, "
+                        f"context {w.ctx}, keep {w.keep_pct}% ({sum(budgets) * w.batch} cached tokens), "
+                        f"compaction every {interval} steps" if interval else
+                        f"{w.name}: attention and appends only",
+            "launch_mode": args.mode, "n_caches": arena.n_caches, "kv_bytes_per_step": state["kv_bytes"] // args.steps,
+            "compactions_in_timed_region": state["compactions"], "track_scores": bool(track),
+        },
+        "us_per_step": round(ms_per_step * 1e3, 1),
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "roofline": {
+            "bound": "hbm", "kernel": "decode_partial", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(),
+            "launches": int(launches), "avg_launch_us": round(avg_launch_s * 1e6, 2),
+            "algorithmic_bytes_per_launch": int(avg_launch_bytes),
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
+    arena.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

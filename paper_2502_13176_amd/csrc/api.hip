@@ -21,7 +21,7 @@ inline bool hip_ok(hipError_t e) {
   return false;
 }
 
-constexpr int kMinChunk = 64;
+constexpr int kMinChunk = 256;
 constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
 constexpr int kDefaultChunk = 1024;
 

@@ -1,0 +1,177 @@
+"""GPU parity: baklava_decode_attn against the fp64 oracle (Eq. 1 / Eq. 7), element by element."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_13176_amd import binding as B
+from paper_2502_13176_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _h():
+    import gpu_harness
+    return gpu_harness
+
+
+def _kernels_for(w):
+    ks = []
+    if w.G <= 8:
+        ks.append(B.KERNEL_VALU)
+    if w.dtype == "bf16" and w.D == 128:
+        ks.append(B.KERNEL_MFMA)
+    return ks
+
+
+def test_tiny_workload_full_cache():
+    H = _h()
+    w = synth.WORKLOADS["tiny"]
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    arena = H.make_arena(w)
+    st = H.fill_from_host(arena, w, [w.ctx] * arena.n_caches, rng, scores="uniform")
+    q, q64 = H.make_q(w, rng, w.L)
+    out = H.gpu_decode(arena, w, q)
+    err = H.check_decode_against_oracle(arena, w, st, q64, out)
+    print(f"tiny: max-abs error {err:.3e}", flush=True)
+    arena.close()
+
+
+@pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+@pytest.mark.parametrize("chunk", [256, 1024, 4096, 16384])
+def test_llama_single_layer_at_full_size(kernel, chunk):
+    """LLaMA-3-8B-shaped layer, context 8192, budgets summing to half of 8*8192, caches at budget."""
+    H = _h()
+    w = synth.WORKLOADS["llama1"]
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    arena = H.make_arena(w, budgets)
+    arena.set_option(B.OPT_KERNEL, kernel)
+    arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+    lens = [budgets[c % w.Hkv] for c in range(arena.n_caches)]
+    st = H.fill_from_host(arena, w, lens, rng)
+    q, q64 = H.make_q(w, rng, w.L)
+    out = H.gpu_decode(arena, w, q)
+    err = H.check_decode_against_oracle(arena, w, st, q64, out)
+    print(f"llama1 kernel={kernel} chunk={chunk}: max-abs error {err:.3e}", flush=True)
+    arena.close()
+
+
+RAGGED_LENS = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 1000, 1023, 1025, 2500]
+
+
+@pytest.mark.parametrize("dtype,D,Hq,Hkv", [
+    ("bf16", 128, 8, 2), ("bf16", 128, 7, 1), ("bf16", 128, 2, 2), ("bf16", 128, 16, 2), ("bf16", 128, 16, 1),
+    ("bf16", 64, 8, 2), ("f32", 64, 4, 2), ("f32", 128, 7, 1), ("f32", 128, 2, 1),
+])
+def test_ragged_lengths_all_shapes(dtype, D, Hq, Hkv):
+    """Lengths around every tile boundary of both kernels, several layers and sequences, with a
+    layer sub-range launch as well as the whole stack."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="ragged", L=2, Hq=Hq, Hkv=Hkv, D=D, batch=2, dtype=dtype,
+                     seed=77, sink=1, recent=1, slack=0)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    n_caches = w.L * w.batch * w.Hkv
+    budgets = [4096] * (w.L * w.Hkv)
+    lens = [RAGGED_LENS[(3 * c + 1) % len(RAGGED_LENS)] for c in range(n_caches)]
+    arena = H.make_arena(w, budgets)
+    st = H.fill_from_host(arena, w, lens, rng)
+    q, q64 = H.make_q(w, rng, w.L)
+    for kernel in _kernels_for(w):
+        arena.set_option(B.OPT_KERNEL, kernel)
+        for chunk in (256, 512, 4096):
+            arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+            out = H.gpu_decode(arena, w, q)
+            H.check_decode_against_oracle(arena, w, st, q64, out)
+        # second layer alone
+        out1 = H.gpu_decode(arena, w, q[1:2], layer_begin=1, layer_count=1)
+        H.check_decode_against_oracle(arena, w, st, q64[1:2], out1, caches=range(n_caches // 2, n_caches),
+                                          layer_begin=1)
+    arena.close()
+
+
+@pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+def test_result_does_not_depend_on_split_factor(kernel):
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="split", Hq=8, Hkv=2, seed=5, slack=0)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = [7000, 3333]
+    arena = H.make_arena(w, budgets)
+    arena.set_option(B.OPT_KERNEL, kernel)
+    st = H.fill_from_host(arena, w, budgets, rng)
+    q, q64 = H.make_q(w, rng, w.L)
+    outs = []
+    for chunk in (8192, 3584, 1024, 256):      # 1, 2, 7 and 28 splits of the long cache
+        arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+        outs.append(H.gpu_decode(arena, w, q))
+        H.check_decode_against_oracle(arena, w, st, q64, outs[-1])
+    for o in outs[1:]:
+        assert np.max(np.abs(o - outs[0])) <= 1e-5
+    arena.close()
+
+
+@pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+def test_peaked_and_large_logits(kernel):
+    """A few keys scaled up so single rows dominate the softmax, and logits of magnitude ~80:
+    the running-max rescaling must stay finite and accurate."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="peaked", Hq=8, Hkv=2, seed=9, slack=0)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = [3000, 1500]
+    arena = H.make_arena(w, budgets)
+    arena.set_option(B.OPT_KERNEL, kernel)
+    st = H.fill_from_host(arena, w, budgets, rng, peaked=True)
+    q, q64 = H.make_q(w, rng, w.L)
+    H.check_decode_against_oracle(arena, w, st, q64, H.gpu_decode(arena, w, q))
+    st = H.fill_from_host(arena, w, budgets, rng, scale=7.0)
+    q, q64 = H.make_q(w, rng, w.L, scale=7.0)
+    H.check_decode_against_oracle(arena, w, st, q64, H.gpu_decode(arena, w, q))
+    # ascending logits: the running maximum changes in every slab
+    n = 2048
+    K = np.zeros((n, w.D), dtype=np.float32)
+    K[:, 0] = np.linspace(-40, 40, n)
+    Vv = rng.standard_normal((n, w.D)).astype(np.float32)
+    arena2 = H.make_arena(synth.shrink(w, Hq=4, Hkv=1), [n])
+    arena2.set_option(B.OPT_KERNEL, kernel)
+    w2 = synth.shrink(w, Hq=4, Hkv=1)
+    st2 = H.HostState(1)
+    st2.K[0], st2.V[0] = synth.f32_to_bf16_bits(K), synth.f32_to_bf16_bits(Vv)
+    arena2.k[:n].copy_(H.to_device_storage(st2.K[0], "bf16", arena2.device))
+    arena2.v[:n].copy_(H.to_device_storage(st2.V[0], "bf16", arena2.device))
+    arena2.set_lengths([n])
+    qq = np.zeros((1, 1, 4, w.D), dtype=np.float32)
+    qq[..., 0] = [11.0, -11.0, 3.0, 0.5]
+    qs = synth.f32_to_bf16_bits(qq)
+    H.check_decode_against_oracle(arena2, w2, st2, synth.storage_to_f64(qs, "bf16"), H.gpu_decode(arena2, w2, qs))
+    arena.close()
+    arena2.close()
+
+
+def test_error_paths():
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="err", Hq=4, Hkv=2, seed=3, slack=2)
+    arena = H.make_arena(w, [300, 200])
+    q = torch.zeros((1, 1, 4, 128), dtype=torch.bfloat16, device=arena.device)
+    out = torch.zeros((1, 1, 4, 128), dtype=torch.float32, device=arena.device)
+    with pytest.raises(B.BaklavaError) as e:           # empty caches
+        arena.decode_attn(0, 1, q, out)
+    assert e.value.status == B.ESTATE
+    with pytest.raises(B.BaklavaError) as e:
+        arena.decode_attn(0, 2, q, out)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.BaklavaError) as e:
+        arena.set_lengths([303, 1])
+    assert e.value.status == B.ECAPACITY
+    arena.set_lengths([302, 1])
+    kn = torch.zeros((1, 2, 128), dtype=torch.bfloat16, device=arena.device)
+    with pytest.raises(B.BaklavaError) as e:           # cache 0 is full
+        arena.append(0, kn, kn, 5)
+    assert e.value.status == B.ECAPACITY
+    assert arena.lengths().tolist() == [302, 1]
+    with pytest.raises(B.BaklavaError) as e:
+        arena.set_option(B.OPT_CHUNK_TOKENS, 100)
+    assert e.value.status == B.EINVAL
+    arena.reset()
+    assert arena.lengths().tolist() == [0, 0]
+    torch.cuda.synchronize()
+    assert arena.len.cpu().tolist() == [0, 0]
+    arena.close()

@@ -140,7 +140,8 @@ int baklava_destroy(baklava_ctx* ctx);
 /* Tuning knobs (tests sweep them; results must not depend on them beyond rounding order). */
 enum {
   BAKLAVA_OPT_CHUNK_TOKENS = 1, /* rows per split-K work item (multiple of 64, >= 256)              */
-  BAKLAVA_OPT_KERNEL = 2        /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
+  BAKLAVA_OPT_KERNEL = 2,       /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
+  BAKLAVA_OPT_TIME_KERNEL = 3   /* 1: bracket every attention partial-kernel launch with HIP events  */
 };
 int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
 
@@ -189,6 +190,15 @@ int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_cou
  */
 int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
                     int32_t* kept_idx_out, void* stream);
+
+/*
+ * Measurement aid for the dominant kernel (the split-K attention partial kernel, which reads all
+ * of the K/V bytes of Eq. 7): with BAKLAVA_OPT_TIME_KERNEL set, baklava_decode_attn records a HIP
+ * event on the caller's stream right before and right after that kernel.  This call waits for
+ * the recorded events, returns the summed elapsed time and the number of launches since the last
+ * read, and clears the record.  total_ms_out, launches_out HOST scalars.
+ */
+int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out);
 
 /* Host mirror of the lengths; len_host_out HOST [n_caches].  No device access. */
 int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);

@@ -19,14 +19,14 @@ LIB_PATH = os.path.join(HERE, "libbaklava.so")
 OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
 BF16, F32 = 0, 1
 POLICY_SCORE, POLICY_STREAMING = 0, 1
-OPT_CHUNK_TOKENS, OPT_KERNEL = 1, 2
+OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL = 1, 2, 3
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
     "baklava_strerror", "baklava_last_hip_error", "baklava_alloc_proportional",
     "baklava_alloc_threshold", "baklava_layout", "baklava_workspace_bytes", "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
-    "baklava_append", "baklava_decode_attn", "baklava_compact", "baklava_lengths",
+    "baklava_append", "baklava_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
 ]
 
 
@@ -77,6 +77,7 @@ def lib() -> C.CDLL:
     L.baklava_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     L.baklava_compact.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.baklava_lengths.argtypes = [C.c_void_p, i32p]
+    L.baklava_profile_read.argtypes = [C.c_void_p, f64p, i64p]
     for name in EXPORTS:
         if name not in ("baklava_strerror", "baklava_workspace_bytes"):
             getattr(L, name).restype = C.c_int
@@ -227,6 +228,11 @@ class Arena:
         ptr = kept_idx_out.data_ptr() if kept_idx_out is not None else None
         _check(lib().baklava_compact(self.ctx, layer_begin, layer_count, ptr, _stream_ptr(stream)),
                "baklava_compact")
+
+    def profile_read(self):
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        _check(lib().baklava_profile_read(self.ctx, C.byref(ms), C.byref(n)), "baklava_profile_read")
+        return float(ms.value), int(n.value)
 
     def lengths(self) -> np.ndarray:
         out = np.zeros(self.n_caches, dtype=np.int32)

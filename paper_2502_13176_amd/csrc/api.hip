@@ -91,6 +91,9 @@ struct baklava_ctx {
   int64_t n_items;
   WorkspacePlan plan;
   char* ws;
+  bool time_kernel;
+  std::vector<hipEvent_t> ev;  // pairs (before, after); the first 2 * ev_used are recorded
+  size_t ev_used;
 };
 
 namespace {
@@ -178,6 +181,8 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
   else ctx->len.assign(n_caches, 0);
   ctx->budget.assign(budget_host, budget_host + m);
   ctx->kernel_pref = 0;
+  ctx->time_kernel = false;
+  ctx->ev_used = 0;
   ctx->plan = plan_workspace(desc, cap_host);
   ctx->ws = reinterpret_cast<char*>(desc->workspace);
   if (desc->workspace_bytes < ctx->plan.total) { delete ctx; return BAKLAVA_ECAPACITY; }
@@ -205,6 +210,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
 
 extern "C" int baklava_destroy(baklava_ctx* ctx) {
   if (!ctx) return BAKLAVA_EINVAL;
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
   return BAKLAVA_OK;
 }
@@ -222,9 +228,28 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       if (value == 1 && ctx->G > 8) return BAKLAVA_EINVAL;
       ctx->kernel_pref = (int32_t)value;
       return BAKLAVA_OK;
+    case BAKLAVA_OPT_TIME_KERNEL:
+      if (value != 0 && value != 1) return BAKLAVA_EINVAL;
+      ctx->time_kernel = value == 1;
+      return BAKLAVA_OK;
     default:
       return BAKLAVA_EINVAL;
   }
+}
+
+extern "C" int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out) {
+  if (!ctx || !total_ms_out || !launches_out) return BAKLAVA_EINVAL;
+  double total = 0.0;
+  for (size_t i = 0; i < ctx->ev_used; ++i) {
+    if (!hip_ok(hipEventSynchronize(ctx->ev[2 * i + 1]))) return BAKLAVA_EHIP;
+    float ms = 0.f;
+    if (!hip_ok(hipEventElapsedTime(&ms, ctx->ev[2 * i], ctx->ev[2 * i + 1]))) return BAKLAVA_EHIP;
+    total += ms;
+  }
+  *total_ms_out = total;
+  *launches_out = (int64_t)ctx->ev_used;
+  ctx->ev_used = 0;
+  return BAKLAVA_OK;
 }
 
 extern "C" int baklava_reset(baklava_ctx* ctx, void* stream) {
@@ -292,9 +317,24 @@ extern "C" int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_
   hipStream_t s = (hipStream_t)stream;
   const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
   const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  if (ctx->time_kernel) {
+    while (ctx->ev.size() < 2 * (ctx->ev_used + 1)) {
+      hipEvent_t e;
+      if (!hip_ok(hipEventCreate(&e))) return BAKLAVA_EHIP;
+      ctx->ev.push_back(e);
+    }
+    ev0 = ctx->ev[2 * ctx->ev_used];
+    ev1 = ctx->ev[2 * ctx->ev_used + 1];
+    if (!hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
+  }
   hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, s)
                           : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
   if (!hip_ok(e)) return BAKLAVA_EHIP;
+  if (ctx->time_kernel) {
+    if (!hip_ok(hipEventRecord(ev1, s))) return BAKLAVA_EHIP;
+    ctx->ev_used += 1;
+  }
   if (!hip_ok(launch_combine(p, ctx->d.D, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
   if (p.track && !hip_ok(launch_score_update(p, i1 - i0, s))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;

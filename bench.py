@@ -102,6 +102,29 @@ def cpu_baseline(arena, w, q_dev, torch, target_seconds):
     }
 
 
+def stream_probe(torch, B, device, nbytes=1 << 32, reps=5):
+    """Bandwidth of the library's trivial streaming kernels on this device (a copy and a
+    read-only sweep of `nbytes`), timed with events on the launch stream."""
+    src = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    dst = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    src.fill_(1)
+    out = {"bytes": nbytes}
+    for mode, name in ((0, "copy"), (1, "read")):
+        B.stream_probe(dst, src, nbytes, mode)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.stream_probe(dst, src, nbytes, mode)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        moved = nbytes * (2 if mode == 0 else 1)
+        out[f"{name}_GBps"] = round(moved / ms / 1e6, 1)
+    del src, dst
+    return out
+
+
 def read_traffic():
     """HBM bytes per launch of the dominant kernel, from the committed counter summary (if any)."""
     path = os.path.join(ROOT, "profiles", "decode_partial_mfma_llama32_pmc.txt")
@@ -143,7 +166,6 @@ def main():
         arena.set_option(B.OPT_KERNEL, args.kernel)
     if args.chunk:
         arena.set_option(B.OPT_CHUNK_TOKENS, args.chunk)
-    arena.set_option(B.OPT_TIME_KERNEL, 1)
 
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     q = torch.randn((w.L, w.batch, w.Hq, w.D), generator=gen, device=arena.device, dtype=torch.float32).to(tdt)
@@ -155,17 +177,14 @@ def main():
     state = {"t": 0, "kv_bytes": 0, "compactions": 0}
     interval = 0 if args.no_compaction else w.interval
 
-    def step():
+    def step(mode):
         state["t"] += 1
         t = state["t"]
-        if args.mode == "layer":
+        if mode == "layer":
             for l in range(w.L):
-                arena.append(l, k_new[l], v_new[l], w.ctx + t)
-                arena.decode_attn(l, 1, q[l], out[l])
+                arena.append_decode_attn(l, 1, k_new[l], v_new[l], w.ctx + t, q[l], out[l])
         else:
-            for l in range(w.L):
-                arena.append(l, k_new[l], v_new[l], w.ctx + t)
-            arena.decode_attn(0, w.L, q, out)
+            arena.append_decode_attn(0, w.L, k_new, v_new, w.ctx + t, q, out)
         state["kv_bytes"] += int(arena.lengths().astype(np.int64).sum()) * w.token_bytes
         if interval and t % interval == 0:
             arena.compact(0, w.L)
@@ -174,26 +193,43 @@ def main():
             # appends only: start again from the budgets before a cache overflows
             arena.set_lengths(lens0)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    arena.profile_read()                      # discard warm-up kernel timings
-    state["kv_bytes"] = 0
-    state["compactions"] = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernel_ms, launches = arena.profile_read()
-    arena.set_option(B.OPT_TIME_KERNEL, 0)
+    def region(n_steps, mode, time_kernel):
+        """n_steps decode steps bracketed by synchronisation; with time_kernel every attention
+        launch is also bracketed by HIP events on the launch stream."""
+        arena.set_option(B.OPT_TIME_KERNEL, 1 if time_kernel else 0)
+        state["kv_bytes"] = 0
+        state["compactions"] = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            step(mode)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernel_ms, launches = arena.profile_read() if time_kernel else (0.0, 0)
+        arena.set_option(B.OPT_TIME_KERNEL, 0)
+        return {"elapsed": elapsed, "kv_bytes": state["kv_bytes"], "compactions": state["compactions"],
+                "kernel_ms": kernel_ms, "launches": launches, "steps": n_steps}
 
+    for _ in range(args.warmup):
+        step(args.mode)
+    # The timed region: exactly `steps` steps, nothing else on the stream.
+    main_r = region(args.steps, args.mode, time_kernel=False)
+    # The same region again with event brackets around every attention launch: the brackets cost a
+    # few microseconds of stream time each, so they stay out of the region `value` comes from.
+    roof_r = region(min(args.steps, 64), args.mode, time_kernel=True)
+    # Upper bound for comparison: all layers in one launch.
+    other = "stack" if args.mode == "layer" else "layer"
+    other_r = region(min(args.steps, 32), other, time_kernel=False)
+
+    elapsed = main_r["elapsed"]
     ms_per_step = elapsed * 1e3 / args.steps
-    gbps = state["kv_bytes"] / elapsed / 1e9
-    avg_launch_bytes = state["kv_bytes"] / max(1, launches)
-    avg_launch_s = kernel_ms * 1e-3 / max(1, launches)
+    gbps = main_r["kv_bytes"] / elapsed / 1e9
+    launches = roof_r["launches"]
+    avg_launch_bytes = roof_r["kv_bytes"] / max(1, launches)
+    avg_launch_s = roof_r["kernel_ms"] * 1e-3 / max(1, launches)
     achieved = avg_launch_bytes / avg_launch_s / 1e9 if launches else 0.0
+    state["kv_bytes"] = main_r["kv_bytes"]
+    state["compactions"] = main_r["compactions"]
 
     result = {
         "metric": "decode-attn KV bytes read/s", "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1,
@@ -217,6 +253,13 @@ def main():
             "algorithmic_bytes_per_launch": int(avg_launch_bytes),
         },
     }
+    result["other_launch_mode"] = {
+        "launch_mode": other, "steps": other_r["steps"],
+        "value": round(other_r["kv_bytes"] / other_r["elapsed"] / 1e9, 2), "unit": "GB/s",
+        "us_per_step": round(other_r["elapsed"] * 1e6 / other_r["steps"], 1),
+        "pct_of_hbm_peak": round(100.0 * other_r["kv_bytes"] / other_r["elapsed"] / 1e9 / HBM_PEAK_GBPS, 2),
+    }
+    result["stream_probe"] = stream_probe(torch, B, arena.device)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
     arena.close()

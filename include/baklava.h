@@ -156,13 +156,14 @@ int baklava_reset(baklava_ctx* ctx, void* stream);
 int baklava_set_lengths(baklava_ctx* ctx, const int32_t* len_host, void* stream);
 
 /*
- * Appends the current token's key and value row to every cache of one layer -- the
- * concatenations [K'; K_t], [V'; V_t] of Eq. 7.  The row's score starts at 0 and its pos is
- * token_pos.  k_new, v_new DEVICE [batch, Hkv, D] in the context's dtype.
- * Errors: EINVAL, ECAPACITY (some cache of the layer is full; nothing is enqueued).
+ * Appends the current token's key and value row to every cache of layers
+ * [layer_begin, layer_begin + layer_count) -- the concatenations [K'; K_t], [V'; V_t] of Eq. 7.
+ * The row's score starts at 0 and its pos is token_pos.
+ * k_new, v_new DEVICE [layer_count, batch, Hkv, D] in the context's dtype, 16-byte aligned.
+ * Errors: EINVAL, ECAPACITY (some cache of the range is full; nothing is enqueued).
  */
-int baklava_append(baklava_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
-                   int32_t token_pos, void* stream);
+int baklava_append(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, const void* k_new,
+                   const void* v_new, int32_t token_pos, void* stream);
 
 /*
  * Single-query attention over the reduced caches (Eq. 7, i.e. Eq. 1 with one query row per
@@ -176,6 +177,16 @@ int baklava_append(baklava_ctx* ctx, int32_t layer, const void* k_new, const voi
  */
 int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
                         const void* q, float* out, void* stream);
+
+/*
+ * baklava_append followed by baklava_decode_attn over the same layer range, as one kernel
+ * launch: the whole of Eq. 7 for one decode step -- the new row joins each cache, then the query
+ * attends over [K'; K_t], [V'; V_t].  Arguments and results as in the two separate calls.
+ * Errors: EINVAL, ECAPACITY (some cache of the range is full; nothing is enqueued).
+ */
+int baklava_append_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                               const void* k_new, const void* v_new, int32_t token_pos,
+                               const void* q, float* out, void* stream);
 
 /*
  * Eviction down to budget (f_evict, Eqs. 5-6: evicted rows vanish, survivors keep their order)
@@ -199,6 +210,16 @@ int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
  * read, and clears the record.  total_ms_out, launches_out HOST scalars.
  */
 int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out);
+
+/*
+ * Measurement aid, independent of any context: streams `bytes` (a multiple of 16) through a
+ * trivial kernel on `stream`.  mode 0 copies src to dst (both DEVICE, `bytes` long, 16-byte
+ * aligned); mode 1 only reads src (dst DEVICE, at least 1 KiB, is not meaningfully written).
+ * Used to calibrate the HBM byte counters against a transfer of known size and to measure the
+ * bandwidth a plain streaming kernel reaches on the same device.
+ * Errors: EINVAL (null, misaligned, bytes not a positive multiple of 16, bad mode), EHIP.
+ */
+int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream);
 
 /* Host mirror of the lengths; len_host_out HOST [n_caches].  No device access. */
 int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);

@@ -26,7 +26,8 @@ EXPORTS = [
     "baklava_strerror", "baklava_last_hip_error", "baklava_alloc_proportional",
     "baklava_alloc_threshold", "baklava_layout", "baklava_workspace_bytes", "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
-    "baklava_append", "baklava_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
+    "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
+    "baklava_stream_probe",
 ]
 
 
@@ -73,11 +74,14 @@ def lib() -> C.CDLL:
     L.baklava_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
     L.baklava_reset.argtypes = [C.c_void_p, C.c_void_p]
     L.baklava_set_lengths.argtypes = [C.c_void_p, i32p, C.c_void_p]
-    L.baklava_append.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    L.baklava_append.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    L.baklava_append_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
     L.baklava_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     L.baklava_compact.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.baklava_lengths.argtypes = [C.c_void_p, i32p]
     L.baklava_profile_read.argtypes = [C.c_void_p, f64p, i64p]
+    L.baklava_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
     for name in EXPORTS:
         if name not in ("baklava_strerror", "baklava_workspace_bytes"):
             getattr(L, name).restype = C.c_int
@@ -216,9 +220,15 @@ class Arena:
         a = _i32(len_host)
         _check(lib().baklava_set_lengths(self.ctx, _p(a, C.c_int32), _stream_ptr(stream)), "baklava_set_lengths")
 
-    def append(self, layer: int, k_new, v_new, token_pos: int, stream=None) -> None:
-        _check(lib().baklava_append(self.ctx, layer, k_new.data_ptr(), v_new.data_ptr(), int(token_pos),
-                                    _stream_ptr(stream)), "baklava_append")
+    def append(self, layer_begin: int, layer_count: int, k_new, v_new, token_pos: int, stream=None) -> None:
+        _check(lib().baklava_append(self.ctx, layer_begin, layer_count, k_new.data_ptr(), v_new.data_ptr(),
+                                    int(token_pos), _stream_ptr(stream)), "baklava_append")
+
+    def append_decode_attn(self, layer_begin: int, layer_count: int, k_new, v_new, token_pos: int, q, out,
+                           stream=None) -> None:
+        _check(lib().baklava_append_decode_attn(self.ctx, layer_begin, layer_count, k_new.data_ptr(),
+                                                v_new.data_ptr(), int(token_pos), q.data_ptr(), out.data_ptr(),
+                                                _stream_ptr(stream)), "baklava_append_decode_attn")
 
     def decode_attn(self, layer_begin: int, layer_count: int, q, out, stream=None) -> None:
         _check(lib().baklava_decode_attn(self.ctx, layer_begin, layer_count, q.data_ptr(), out.data_ptr(),
@@ -238,3 +248,9 @@ class Arena:
         out = np.zeros(self.n_caches, dtype=np.int32)
         _check(lib().baklava_lengths(self.ctx, _p(out, C.c_int32)), "baklava_lengths")
         return out
+
+
+def stream_probe(dst, src, nbytes: int, mode: int, stream=None) -> None:
+    """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only)."""
+    _check(lib().baklava_stream_probe(dst.data_ptr(), src.data_ptr(), int(nbytes), int(mode),
+                                      _stream_ptr(stream)), "baklava_stream_probe")

@@ -10,12 +10,13 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libbaklava.so")
 
-SOURCES = ["host_alloc.cpp", "api.hip", "decode_valu.hip", "decode_mfma.hip", "compact.hip"]
+SOURCES = ["host_alloc.cpp", "api.hip", "decode_valu.hip", "decode_mfma.hip", "compact.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 arithmetic is kept off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",  # MFMA accumulators stay in VGPRs (no AGPR copies)
     "-Wno-unused-command-line-argument",
 ]
 

@@ -23,7 +23,8 @@ inline bool hip_ok(hipError_t e) {
 
 constexpr int kMinChunk = 256;
 constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
-constexpr int kDefaultChunk = 1024;
+constexpr int kDefaultChunk = 512;
+constexpr int kMaxChunk = 1 << 22; // row offsets inside a work item stay below 2^32 bytes
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -34,7 +35,8 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 }
 
 struct WorkspacePlan {
-  size_t items, cib, part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, total;
+  size_t items, cib, part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, iorder_all,
+      iorder_layer, multi_all, multi_layer, total;
   int64_t max_items;
 };
 
@@ -61,16 +63,20 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
   for (int64_t c = 0; c < n_caches; ++c) total_tokens += cap[c];
   w.max_items = count_items(cap, n_caches, kSizingChunk);
   size_t o = 0;
-  w.items = o;       o = align256(o + (size_t)w.max_items * sizeof(Item));
-  w.cib = o;         o = align256(o + (size_t)(n_caches + 1) * 4);
-  w.part_o = o;      o = align256(o + (size_t)w.max_items * G * d->D * 4);
-  w.part_ml = o;     o = align256(o + (size_t)w.max_items * G * 2 * 4);
-  w.final_ml = o;    o = align256(o + (size_t)n_caches * G * 2 * 4);
-  w.logits = o;      o = align256(o + (d->track_scores ? (size_t)total_tokens * G * 4 : 0));
-  w.kept = o;        o = align256(o + (size_t)total_tokens * 4);
-  w.info = o;        o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
-  w.order_all = o;   o = align256(o + (size_t)n_caches * 4);
-  w.order_layer = o; o = align256(o + (size_t)n_caches * 4);
+  w.items = o;        o = align256(o + (size_t)w.max_items * sizeof(Item));
+  w.cib = o;          o = align256(o + (size_t)(n_caches + 1) * 4);
+  w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
+  w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
+  w.final_ml = o;     o = align256(o + (size_t)n_caches * G * 2 * 4);
+  w.logits = o;       o = align256(o + (d->track_scores ? (size_t)total_tokens * G * 4 : 0));
+  w.kept = o;         o = align256(o + (size_t)total_tokens * 4);
+  w.info = o;         o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
+  w.order_all = o;    o = align256(o + (size_t)n_caches * 4);
+  w.order_layer = o;  o = align256(o + (size_t)n_caches * 4);
+  w.iorder_all = o;   o = align256(o + (size_t)w.max_items * 4);
+  w.iorder_layer = o; o = align256(o + (size_t)w.max_items * 4);
+  w.multi_all = o;    o = align256(o + (size_t)n_caches * 4);
+  w.multi_layer = o;  o = align256(o + (size_t)n_caches * 4);
   w.total = o;
   return w;
 }
@@ -85,9 +91,12 @@ struct baklava_ctx {
   int32_t row_bytes;
   std::vector<int64_t> off;
   std::vector<int32_t> cap, len, budget;
+  std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
   int32_t chunk;
   int32_t kernel_pref;
   std::vector<int32_t> cib;  // cache -> first item
+  std::vector<int32_t> multi_begin;  // layer -> first entry of the per-layer list of multi-item caches
+  int32_t n_multi;
   int64_t n_items;
   WorkspacePlan plan;
   char* ws;
@@ -100,6 +109,8 @@ namespace {
 
 // Cuts every cache into runs of `chunk` rows over its whole capacity.  The table depends on the
 // capacities only, so it is uploaded once; the kernels clamp each run to the live length.
+// Two launch orders are kept, both with the items of long caches first: one over the whole
+// model, one inside each layer so that a layer range is a contiguous slice.
 int build_schedule(baklava_ctx* ctx, int chunk) {
   std::vector<Item> items;
   std::vector<int32_t> cib(ctx->n_caches + 1);
@@ -119,20 +130,109 @@ int build_schedule(baklava_ctx* ctx, int chunk) {
   }
   cib[ctx->n_caches] = (int32_t)items.size();
   if ((int64_t)items.size() > ctx->plan.max_items) return BAKLAVA_ECAPACITY;
+  std::vector<int32_t> io_all, io_layer;
+  io_all.reserve(items.size());
+  io_layer.reserve(items.size());
+  for (int32_t c : ctx->order_all)
+    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) io_all.push_back(i);
+  for (int32_t c : ctx->order_layer)
+    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) io_layer.push_back(i);
+  // Caches with more than one work item need the combine kernel; same two orders.
+  std::vector<int32_t> multi_all, multi_layer, multi_begin(ctx->d.L + 1, 0);
+  for (int32_t c : ctx->order_all)
+    if (cib[c + 1] - cib[c] > 1) multi_all.push_back(c);
+  for (int32_t c : ctx->order_layer) {
+    if (cib[c + 1] - cib[c] > 1) {
+      multi_layer.push_back(c);
+      multi_begin[c / ctx->cpl + 1] += 1;
+    }
+  }
+  for (int32_t l = 0; l < ctx->d.L; ++l) multi_begin[l + 1] += multi_begin[l];
   if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items, items.data(), items.size() * sizeof(Item),
-                        hipMemcpyHostToDevice)))
+  const size_t ni = items.size();
+  if (!multi_all.empty() &&
+      (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi_all, multi_all.data(), multi_all.size() * 4, hipMemcpyHostToDevice)) ||
+       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi_layer, multi_layer.data(), multi_layer.size() * 4, hipMemcpyHostToDevice))))
     return BAKLAVA_EHIP;
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib, cib.data(), cib.size() * 4, hipMemcpyHostToDevice)))
+  ctx->multi_begin.swap(multi_begin);
+  ctx->n_multi = (int32_t)multi_all.size();
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items, items.data(), ni * sizeof(Item), hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib, cib.data(), cib.size() * 4, hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder_all, io_all.data(), ni * 4, hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder_layer, io_layer.data(), ni * 4, hipMemcpyHostToDevice)))
     return BAKLAVA_EHIP;
   ctx->cib.swap(cib);
-  ctx->n_items = (int64_t)items.size();
+  ctx->n_items = (int64_t)ni;
   ctx->chunk = chunk;
   return BAKLAVA_OK;
 }
 
 bool range_ok(const baklava_ctx* ctx, int32_t lb, int32_t lc) {
   return lb >= 0 && lc > 0 && (int64_t)lb + lc <= ctx->d.L;
+}
+
+int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, const void* k_new,
+                const void* v_new, int32_t token_pos, const void* q, float* out, void* stream) {
+  const bool fused = k_new != nullptr;
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  for (int64_t c = c0; c < c1; ++c) {
+    if (fused && ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
+    if (!fused && ctx->len[c] <= 0) return BAKLAVA_ESTATE;
+  }
+  const int32_t i0 = ctx->cib[c0], i1 = ctx->cib[c1];
+  const bool whole = layer_begin == 0 && layer_count == ctx->d.L;
+  DecodeParams p;
+  p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
+  p.off = ctx->d.off; p.len = ctx->d.len;
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items);
+  // Items are numbered cache by cache, so a layer range is the slice [i0, i1) of the per-layer order.
+  p.order = whole ? reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder_all)
+                  : reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder_layer) + i0;
+  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib);
+  p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
+  p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
+  p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
+  p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
+  p.score = ctx->d.score;
+  p.pos = ctx->d.pos;
+  const int32_t m0 = ctx->multi_begin[layer_begin], m1 = ctx->multi_begin[layer_begin + layer_count];
+  p.multi = whole ? reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi_all)
+                  : reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi_layer) + m0;
+  p.k_new = k_new; p.v_new = v_new;
+  p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
+  p.cache_begin = (int32_t)c0;
+  p.track = ctx->d.track_scores ? 1 : 0;
+  p.fused_append = fused ? 1 : 0;
+  p.token_pos = token_pos;
+  p.row_bytes = ctx->row_bytes;
+  p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
+  hipStream_t s = (hipStream_t)stream;
+  const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
+  const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  if (ctx->time_kernel) {
+    while (ctx->ev.size() < 2 * (ctx->ev_used + 1)) {
+      hipEvent_t e;
+      if (!hip_ok(hipEventCreate(&e))) return BAKLAVA_EHIP;
+      ctx->ev.push_back(e);
+    }
+    ev0 = ctx->ev[2 * ctx->ev_used];
+    ev1 = ctx->ev[2 * ctx->ev_used + 1];
+    if (!hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
+  }
+  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, s)
+                          : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
+  if (!hip_ok(e)) return BAKLAVA_EHIP;
+  if (ctx->time_kernel) {
+    if (!hip_ok(hipEventRecord(ev1, s))) return BAKLAVA_EHIP;
+    ctx->ev_used += 1;
+  }
+  if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
+  if (fused)
+    for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
+  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, s))) return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
 }
 
 }  // namespace
@@ -187,23 +287,22 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
   ctx->ws = reinterpret_cast<char*>(desc->workspace);
   if (desc->workspace_bytes < ctx->plan.total) { delete ctx; return BAKLAVA_ECAPACITY; }
 
+  // Launch orders: longest caches first, over the whole model and within each layer.
+  auto longer = [&](int32_t a, int32_t b) { return ctx->cap[a] > ctx->cap[b]; };
+  ctx->order_all.resize(n_caches);
+  std::iota(ctx->order_all.begin(), ctx->order_all.end(), 0);
+  ctx->order_layer = ctx->order_all;
+  std::stable_sort(ctx->order_all.begin(), ctx->order_all.end(), longer);
+  for (int32_t l = 0; l < desc->L; ++l)
+    std::stable_sort(ctx->order_layer.begin() + (int64_t)l * ctx->cpl,
+                     ctx->order_layer.begin() + (int64_t)(l + 1) * ctx->cpl, longer);
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_all, ctx->order_all.data(), n_caches * 4, hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_layer, ctx->order_layer.data(), n_caches * 4, hipMemcpyHostToDevice))) {
+    delete ctx;
+    return BAKLAVA_EHIP;
+  }
   int st = build_schedule(ctx, kDefaultChunk);
   if (st != BAKLAVA_OK) { delete ctx; return st; }
-
-  // Launch orders for eviction: longest caches first, over the whole model and within each layer.
-  std::vector<int32_t> order(n_caches);
-  std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return ctx->cap[a] > ctx->cap[b]; });
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_all, order.data(), n_caches * 4, hipMemcpyHostToDevice))) {
-    delete ctx; return BAKLAVA_EHIP;
-  }
-  std::iota(order.begin(), order.end(), 0);
-  for (int32_t l = 0; l < desc->L; ++l)
-    std::stable_sort(order.begin() + (int64_t)l * ctx->cpl, order.begin() + (int64_t)(l + 1) * ctx->cpl,
-                     [&](int32_t a, int32_t b) { return ctx->cap[a] > ctx->cap[b]; });
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_layer, order.data(), n_caches * 4, hipMemcpyHostToDevice))) {
-    delete ctx; return BAKLAVA_EHIP;
-  }
   *out = ctx;
   return BAKLAVA_OK;
 }
@@ -219,7 +318,7 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
   if (!ctx) return BAKLAVA_EINVAL;
   switch (option) {
     case BAKLAVA_OPT_CHUNK_TOKENS:
-      if (value < kMinChunk || value % 64 || value > (int64_t)1 << 24) return BAKLAVA_EINVAL;
+      if (value < kMinChunk || value % 64 || value > kMaxChunk) return BAKLAVA_EINVAL;
       if ((int32_t)value == ctx->chunk) return BAKLAVA_OK;
       return build_schedule(ctx, (int32_t)value);
     case BAKLAVA_OPT_KERNEL:
@@ -274,20 +373,21 @@ extern "C" int baklava_set_lengths(baklava_ctx* ctx, const int32_t* len_host, vo
   return BAKLAVA_OK;
 }
 
-extern "C" int baklava_append(baklava_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
-                              int32_t token_pos, void* stream) {
-  if (!ctx || !k_new || !v_new || layer < 0 || layer >= ctx->d.L) return BAKLAVA_EINVAL;
+extern "C" int baklava_append(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                              const void* k_new, const void* v_new, int32_t token_pos, void* stream) {
+  if (!ctx || !k_new || !v_new || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
   if (((uintptr_t)k_new | (uintptr_t)v_new) & 15) return BAKLAVA_EINVAL;
-  const int64_t c0 = (int64_t)layer * ctx->cpl;
-  for (int64_t c = c0; c < c0 + ctx->cpl; ++c)
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  for (int64_t c = c0; c < c1; ++c)
     if (ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
   AppendParams p;
   p.k = ctx->d.k; p.v = ctx->d.v; p.score = ctx->d.score; p.pos = ctx->d.pos;
   p.off = ctx->d.off; p.cap = ctx->d.cap; p.len = ctx->d.len;
   p.k_new = k_new; p.v_new = v_new;
   p.cache_begin = (int32_t)c0; p.token_pos = token_pos; p.row_bytes = ctx->row_bytes;
-  if (!hip_ok(launch_append(p, ctx->cpl, (hipStream_t)stream))) return BAKLAVA_EHIP;
-  for (int64_t c = c0; c < c0 + ctx->cpl; ++c) ctx->len[c] += 1;
+  if (!hip_ok(launch_append(p, (int)(c1 - c0), (hipStream_t)stream))) return BAKLAVA_EHIP;
+  for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
   return BAKLAVA_OK;
 }
 
@@ -295,49 +395,15 @@ extern "C" int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_
                                    const void* q, float* out, void* stream) {
   if (!ctx || !q || !out || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
   if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return BAKLAVA_EINVAL;
-  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
-  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
-  for (int64_t c = c0; c < c1; ++c)
-    if (ctx->len[c] <= 0) return BAKLAVA_ESTATE;
-  const int32_t i0 = ctx->cib[c0], i1 = ctx->cib[c1];
-  DecodeParams p;
-  p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
-  p.off = ctx->d.off; p.len = ctx->d.len;
-  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items) + i0;
-  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib);
-  p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
-  p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
-  p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
-  p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
-  p.score = ctx->d.score;
-  p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
-  p.cache_begin = (int32_t)c0;
-  p.track = ctx->d.track_scores ? 1 : 0;
-  p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
-  hipStream_t s = (hipStream_t)stream;
-  const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
-  const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
-  hipEvent_t ev0 = nullptr, ev1 = nullptr;
-  if (ctx->time_kernel) {
-    while (ctx->ev.size() < 2 * (ctx->ev_used + 1)) {
-      hipEvent_t e;
-      if (!hip_ok(hipEventCreate(&e))) return BAKLAVA_EHIP;
-      ctx->ev.push_back(e);
-    }
-    ev0 = ctx->ev[2 * ctx->ev_used];
-    ev1 = ctx->ev[2 * ctx->ev_used + 1];
-    if (!hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
-  }
-  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, s)
-                          : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
-  if (!hip_ok(e)) return BAKLAVA_EHIP;
-  if (ctx->time_kernel) {
-    if (!hip_ok(hipEventRecord(ev1, s))) return BAKLAVA_EHIP;
-    ctx->ev_used += 1;
-  }
-  if (!hip_ok(launch_combine(p, ctx->d.D, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
-  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, s))) return BAKLAVA_EHIP;
-  return BAKLAVA_OK;
+  return decode_impl(ctx, layer_begin, layer_count, nullptr, nullptr, 0, q, out, stream);
+}
+
+extern "C" int baklava_append_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                                          const void* k_new, const void* v_new, int32_t token_pos,
+                                          const void* q, float* out, void* stream) {
+  if (!ctx || !q || !out || !k_new || !v_new || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
+  if (((uintptr_t)q | (uintptr_t)out | (uintptr_t)k_new | (uintptr_t)v_new) & 15) return BAKLAVA_EINVAL;
+  return decode_impl(ctx, layer_begin, layer_count, k_new, v_new, token_pos, q, out, stream);
 }
 
 extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
@@ -370,5 +436,12 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
 extern "C" int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out) {
   if (!ctx || !len_host_out) return BAKLAVA_EINVAL;
   std::memcpy(len_host_out, ctx->len.data(), ctx->n_caches * sizeof(int32_t));
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream) {
+  if (!dst || !src || bytes <= 0 || (bytes & 15) || (mode != 0 && mode != 1)) return BAKLAVA_EINVAL;
+  if (((uintptr_t)dst | (uintptr_t)src) & 15) return BAKLAVA_EINVAL;
+  if (!hip_ok(launch_stream_probe(dst, src, bytes, mode, (hipStream_t)stream))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;
 }

@@ -22,22 +22,30 @@ struct CompactInfo {
 };
 
 struct DecodeParams {
-  const void* k;
-  const void* v;
+  void* k;
+  void* v;
   const void* q;
   float* out;
   const int64_t* off;
-  const int32_t* len;
-  const Item* items;               // first item of the launched range
+  int32_t* len;
+  const Item* items;               // whole table, indexed by item id
+  const int32_t* order;            // launch order of the launched range: blockIdx.x -> item id
   const int32_t* cache_item_begin; // [n_caches + 1], absolute item index
   float* part_o;                   // [n_items, G, D] un-normalised partial outputs
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
   float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
   float* logits;                   // [total_tokens, G] scaled logits in log2 units (track_scores)
   float* score;
+  int32_t* pos;
+  const int32_t* multi;            // caches of the launched range that have more than one work item
+  const void* k_new;               // fused append: [caches of the range, D] rows to add first
+  const void* v_new;
   int32_t G, Hq, Hkv, batch;
   int32_t cache_begin;             // first cache id of the launched range
   int32_t track;
+  int32_t fused_append;            // 1: every cache of the range first receives its new row
+  int32_t token_pos;
+  int32_t row_bytes;
   float scale_log2e;               // log2(e) / sqrt(D)
 };
 
@@ -76,12 +84,13 @@ struct CompactParams {
 // Launchers (defined next to their kernels).  All return hipError_t of the launch.
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s);
-hipError_t launch_combine(const DecodeParams& p, int D, int n_caches, hipStream_t s);
+hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s);
 hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
 hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s);
 hipError_t launch_compact_move(const CompactParams& p, int n_caches, hipStream_t s);
+hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mode, hipStream_t s);
 
 }  // namespace baklava
 #endif

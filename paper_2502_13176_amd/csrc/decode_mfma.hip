@@ -20,6 +20,7 @@
 // Each of the 4 wavefronts of a workgroup streams its own 32-row slabs and owns a private LDS
 // region: there is no barrier inside the loop.
 #include "common.h"
+#include "decode_tail.h"
 
 namespace baklava {
 
@@ -37,21 +38,21 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-union Frag {
-  uint4 u;
-  bf16x8_t v;
-  uint32_t w[4];
-  uint16_t h[8];
-};
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_cast(bf16x8_t, x); }
 
 __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
 
-  const Item it = p.items[blockIdx.x];
+  const Item it = p.items[p.order[blockIdx.x]];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, jg = lane >> 4;
   const int G = p.G;
-  const int n = p.len[it.c];
+  const int n_old = p.len[it.c];
+  const int n = n_old + p.fused_append;
+  if (p.fused_append) append_new_row(p, it, n_old);
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
   const int64_t row0 = p.off[it.c] + it.start;
@@ -63,14 +64,14 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
   const int64_t qrow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
 
   // B operand of the first product: lane (g, j), chunk c holds Q[g][32c + 8j .. +8).
-  Frag qb[4];
+  bf16x8_t qb[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
+    u32x4_t raw = {0u, 0u, 0u, 0u};
     if (n16 < G)
-      qb[c].u = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(p.q) +
-                                                (qrow0 + n16) * (kD * 2) + c * 64 + jg * 16);
-    else
-      qb[c].u = make_uint4(0, 0, 0, 0);
+      raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(p.q) +
+                                              (qrow0 + n16) * (kD * 2) + c * 64 + jg * 16);
+    qb[c] = as_bf16x8(raw);
   }
 
   floatx4_t o[8];
@@ -80,40 +81,53 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
   float l_part = 0.f;     // this lane's share of the running sum
   const float cs = p.scale_log2e;
 
-  for (int t0 = wave * kSlab; t0 < cnt; t0 += kWaves * kSlab) {
-    // ---- loads: K straight into the A layout, V in whole rows (fully coalesced) -------------
-    Frag kr[2][4];
-#pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      const int r = min(t0 + T * 16 + n16, cnt - 1);
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        kr[T][c].u = *reinterpret_cast<const uint4*>(Kb + (int64_t)r * (kD * 2) + c * 64 + jg * 16);
-    }
-    uint4 vr[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = min(t0 + jg + 4 * i, cnt - 1);
-      vr[i] = *reinterpret_cast<const uint4*>(Vb + (int64_t)r * (kD * 2) + n16 * 16);
-    }
+  // Row indices are clamped to the last live row of the work item, so nothing outside the live
+  // rows is ever read; a clamped row's softmax weight is forced to zero below.  Offsets from the
+  // item's first row fit 32 bits (a work item spans < 2^23 rows).
+  const int last = cnt - 1;
+  const uint32_t k_lane = jg * 16, v_lane = n16 * 16;
+  u32x4_t kr[2][4];
+  u32x4_t vr[8];
 
-    // ---- S^T = K Q^T --------------------------------------------------------------------------
+#define BAKLAVA_LOAD_K(T0)                                                                        \
+  _Pragma("unroll") for (int T = 0; T < 2; ++T) {                                                 \
+    const uint32_t off = (uint32_t)min((T0) + T * 16 + n16, last) * (kD * 2) + k_lane;            \
+    _Pragma("unroll") for (int c = 0; c < 4; ++c)                                                 \
+        kr[T][c] = *reinterpret_cast<const u32x4_t*>(Kb + off + c * 64);                          \
+  }
+#define BAKLAVA_LOAD_V(T0)                                                                        \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                 \
+    const uint32_t off = (uint32_t)min((T0) + jg + 4 * i, last) * (kD * 2) + v_lane;              \
+    vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + off);                                          \
+  }
+
+  int t0 = wave * kSlab;
+  if (t0 < cnt) {
+    BAKLAVA_LOAD_K(t0)
+    BAKLAVA_LOAD_V(t0)
+  }
+  for (; t0 < cnt; t0 += kWaves * kSlab) {
+    const int tn = t0 + kWaves * kSlab;
+
+    // ---- S^T = K Q^T, then the next slab's K loads reuse the registers ------------------------
     floatx4_t s[2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
       s[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        s[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[T][c].v, qb[c].v, s[T], 0, 0, 0);
+        s[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kr[T][c]), qb[c], s[T], 0, 0, 0);
     }
+    BAKLAVA_LOAD_K(tn)  // past the end every row clamps to the last live row: harmless re-reads
 
-    // ---- stage V rows in LDS ------------------------------------------------------------------
+    // ---- stage V rows in LDS, then the next slab's V loads reuse the registers ----------------
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       unsigned char* dst = myl + (jg + 4 * i) * kVStride + n16 * 16;
-      *reinterpret_cast<uint2*>(dst) = make_uint2(vr[i].x, vr[i].y);
-      *reinterpret_cast<uint2*>(dst + 8) = make_uint2(vr[i].z, vr[i].w);
+      *reinterpret_cast<u32x2_t*>(dst) = u32x2_t{vr[i].x, vr[i].y};
+      *reinterpret_cast<u32x2_t*>(dst + 8) = u32x2_t{vr[i].z, vr[i].w};
     }
+    BAKLAVA_LOAD_V(tn)
 
     // ---- online softmax on the accumulator layout --------------------------------------------
     float x[8];
@@ -150,17 +164,16 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
 #pragma unroll
       for (int b = 0; b < 8; ++b) o[b] *= alpha;
     }
-    Frag ph, pl;
+    u32x4_t ph;
+    bf16x8_t pl;
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
       const float p0 = fast_exp2(x[e] - m_run), p1 = fast_exp2(x[e + 1] - m_run);
       l_part += p0 + p1;
       const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-      ph.w[e / 2] = (u0 >> 16) | (u1 & 0xffff0000u);  // truncated high parts
-      const float r0 = p0 - __uint_as_float(u0 & 0xffff0000u);
-      const float r1 = p1 - __uint_as_float(u1 & 0xffff0000u);
-      pl.v[e] = (__bf16)r0;
-      pl.v[e + 1] = (__bf16)r1;
+      ph[e / 2] = (u0 >> 16) | (u1 & 0xffff0000u);  // truncated high parts
+      pl[e] = (__bf16)(p0 - __uint_as_float(u0 & 0xffff0000u));
+      pl[e + 1] = (__bf16)(p1 - __uint_as_float(u1 & 0xffff0000u));
     }
 
     // ---- O^T += V^T P^T -----------------------------------------------------------------------
@@ -169,25 +182,29 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-      Frag a;
+      u32x4_t a;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = (e / 4) * 16 + jg * 4 + (e % 4);
-        a.h[e] = *reinterpret_cast<const uint16_t*>(myl + row * kVStride + (b * 16 + n16) * 2);
+      for (int e = 0; e < 8; e += 2) {
+        const int r0 = (e / 4) * 16 + jg * 4 + (e % 4);
+        const uint32_t lo = *reinterpret_cast<const uint16_t*>(myl + r0 * kVStride + (b * 16 + n16) * 2);
+        const uint32_t hi = *reinterpret_cast<const uint16_t*>(myl + (r0 + 1) * kVStride + (b * 16 + n16) * 2);
+        a[e / 2] = lo | (hi << 16);
       }
-      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, ph.v, o[b], 0, 0, 0);
-      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, pl.v, o[b], 0, 0, 0);
+      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(ph), o[b], 0, 0, 0);
+      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), pl, o[b], 0, 0, 0);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
+#undef BAKLAVA_LOAD_K
+#undef BAKLAVA_LOAD_V
 
   // Sum of the four lanes of a head.
   float l_tot = l_part;
   l_tot += __shfl_xor(l_tot, 16);
   l_tot += __shfl_xor(l_tot, 32);
 
-  // Merge the four wavefronts through LDS (reusing the staging area) and write the partial.
+  // Hand the four wavefronts' results over through LDS (reusing the staging area).
   __syncthreads();
   float* sm_o = reinterpret_cast<float*>(lds);                    // [kWaves][16][kD]
   float* sm_m = sm_o + kWaves * 16 * kD;                          // [kWaves][16]
@@ -204,25 +221,7 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * kD; idx += 256) {
-    const int g = idx / kD, d = idx % kD;
-    float mm = sm_m[g];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) mm = fmaxf(mm, sm_m[w * 16 + g]);
-    const float ms = (mm == kNegInf) ? 0.f : mm;
-    float ll = 0.f, oo = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float a = fast_exp2(sm_m[w * 16 + g] - ms);
-      ll += sm_l[w * 16 + g] * a;
-      oo += sm_o[(w * 16 + g) * kD + d] * a;
-    }
-    p.part_o[((int64_t)it.slot * G + g) * kD + d] = oo;
-    if (d == 0) {
-      p.part_ml[((int64_t)it.slot * G + g) * 2 + 0] = mm;
-      p.part_ml[((int64_t)it.slot * G + g) * 2 + 1] = ll;
-    }
-  }
+  finish_item<kD, 16>(p, it, G, n, sm_o, sm_m, sm_l);
 }
 
 }  // namespace

@@ -7,6 +7,7 @@
 // every query head of the group (online softmax, Eq. 1 re-associated) and the groups are merged
 // once at the end: no barrier and no cross-group traffic inside the streaming loop.
 #include "common.h"
+#include "decode_tail.h"
 
 namespace baklava {
 
@@ -56,11 +57,13 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
   constexpr int TILE = RPW * U;
   constexpr int NW = 4;
 
-  const Item it = p.items[blockIdx.x];
+  const Item it = p.items[p.order[blockIdx.x]];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rg = lane / LPR;
   const int G = p.G;
-  const int n = p.len[it.c];
+  const int n_old = p.len[it.c];
+  const int n = n_old + p.fused_append;
+  if (p.fused_append) append_new_row(p, it, n_old);
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
   const int64_t row0 = p.off[it.c] + it.start;
@@ -163,81 +166,81 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
     }
   }
 
-  // Merge the four wavefronts through LDS and write the item's partial.
-  __shared__ float sm_m[NW][GT], sm_l[NW][GT];
-  __shared__ float sm_acc[NW][GT][D];
+  // Hand the four wavefronts' results over through LDS.
+  __shared__ float sm[NW * GT * D + 2 * NW * GT];
+  float* sm_o = sm;                  // [NW][GT][D]
+  float* sm_m = sm + NW * GT * D;    // [NW][GT]
+  float* sm_l = sm_m + NW * GT;      // [NW][GT]
   if (rg == 0) {
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      if (sub == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+      if (sub == 0) { sm_m[wave * GT + g] = m[g]; sm_l[wave * GT + g] = l[g]; }
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) sm_acc[wave][g][sub * EPL + e] = acc[g][e];
+      for (int e = 0; e < EPL; ++e) sm_o[(wave * GT + g) * D + sub * EPL + e] = acc[g][e];
     }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-    const int g = idx / D, d = idx % D;
-    float mm = sm_m[0][g];
+  finish_item<D, GT>(p, it, G, n, sm_o, sm_m, sm_l);
+}
+
+// Merge of the split partials of one (cache, query head):
+//   out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M)
+// which is the softmax of Eq. 7 with the sum over rows regrouped by split.  One workgroup per
+// (cache with several work items, query head); 256 / D thread groups share the splits.
+template <int D>
+__global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
+  constexpr int GROUPS = 256 / D;
+  const int G = p.G;
+  const int c = p.multi[blockIdx.x / G];
+  const int g = blockIdx.x % G;
+  const int tid = threadIdx.x;
+  const int d = tid % D, grp = tid / D;
+  const int ib = p.cache_item_begin[c], ie = p.cache_item_begin[c + 1];
+  float m = kNegInf, l = 0.f, o = 0.f;
+#pragma unroll 8
+  for (int s = ib + grp; s < ie; s += GROUPS) {
+    const float ms = p.part_ml[((int64_t)s * G + g) * 2];
+    const float ls = p.part_ml[((int64_t)s * G + g) * 2 + 1];
+    const float os = p.part_o[((int64_t)s * G + g) * D + d];
+    const float mn = fmaxf(m, ms);
+    const float msafe = (mn == kNegInf) ? 0.f : mn;
+    const float a = fast_exp2(m - msafe), b = fast_exp2(ms - msafe);
+    l = l * a + ls * b;
+    o = o * a + os * b;
+    m = mn;
+  }
+  __shared__ float red_o[GROUPS][D], red_m[GROUPS], red_l[GROUPS];
+  red_o[grp][d] = o;
+  if (d == 0) { red_m[grp] = m; red_l[grp] = l; }
+  __syncthreads();
+  if (grp == 0) {
+    float mm = red_m[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, sm_m[w][g]);
+    for (int w = 1; w < GROUPS; ++w) mm = fmaxf(mm, red_m[w]);
     const float ms = (mm == kNegInf) ? 0.f : mm;
     float ll = 0.f, oo = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      const float a = fast_exp2(sm_m[w][g] - ms);
-      ll += sm_l[w][g] * a;
-      oo += sm_acc[w][g][d] * a;
+    for (int w = 0; w < GROUPS; ++w) {
+      const float a = fast_exp2(red_m[w] - ms);
+      ll += red_l[w] * a;
+      oo += red_o[w][d] * a;
     }
-    p.part_o[((int64_t)it.slot * G + g) * D + d] = oo;
+    const float inv = 1.f / ll;
+    const int c_rel = c - p.cache_begin;
+    const int64_t orow = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G + g;
+    p.out[orow * D + d] = oo * inv;
     if (d == 0) {
-      p.part_ml[((int64_t)it.slot * G + g) * 2 + 0] = mm;
-      p.part_ml[((int64_t)it.slot * G + g) * 2 + 1] = ll;
+      p.final_ml[((int64_t)c * G + g) * 2 + 0] = ms;
+      p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
+      if (g == 0 && p.fused_append) p.len[c] += 1;  // the fused append's row is now counted
     }
-  }
-}
-
-// out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M): the same softmax as Eq. 7, with the sum
-// over rows regrouped by split.  One wavefront per (cache, query head).
-template <int D>
-__global__ __launch_bounds__(64) void combine_kernel(DecodeParams p) {
-  const int G = p.G;
-  const int c = p.cache_begin + blockIdx.x / G;
-  const int g = blockIdx.x % G;
-  const int lane = threadIdx.x;
-  const int ib = p.cache_item_begin[c], ie = p.cache_item_begin[c + 1];
-  float M = kNegInf;
-  for (int s = ib + lane; s < ie; s += 64) M = fmaxf(M, p.part_ml[((int64_t)s * G + g) * 2]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-  const float Ms = (M == kNegInf) ? 0.f : M;
-  constexpr int PER = D / 64;
-  float o[PER];
-#pragma unroll
-  for (int i = 0; i < PER; ++i) o[i] = 0.f;
-  float Lsum = 0.f;
-  for (int s = ib; s < ie; ++s) {
-    const float ms = p.part_ml[((int64_t)s * G + g) * 2];
-    const float ls = p.part_ml[((int64_t)s * G + g) * 2 + 1];
-    const float a = fast_exp2(ms - Ms);
-    Lsum += ls * a;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) o[i] += p.part_o[((int64_t)s * G + g) * D + lane + 64 * i] * a;
-  }
-  const float inv = 1.f / Lsum;
-  const int c_rel = c - p.cache_begin;
-  const int64_t orow = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G + g;
-#pragma unroll
-  for (int i = 0; i < PER; ++i) p.out[orow * D + lane + 64 * i] = o[i] * inv;
-  if (lane == 0) {
-    p.final_ml[((int64_t)c * G + g) * 2 + 0] = Ms;
-    p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
   }
 }
 
 // score_j += sum_g 2^(s_gj - M_g) / L_g  (cumulative attention per cached token, summed over the
 // query heads that share the cache).
 __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
-  const Item it = p.items[blockIdx.x];
+  const Item it = p.items[p.order[blockIdx.x]];
   const int G = p.G;
   const int n = p.len[it.c];
   const int cnt = min(it.start + it.count, n) - it.start;
@@ -302,9 +305,9 @@ hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_ite
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_combine(const DecodeParams& p, int D, int n_caches, hipStream_t s) {
-  if (n_caches <= 0) return hipSuccess;
-  const dim3 grid(n_caches * p.G), block(64);
+hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s) {
+  if (n_multi <= 0) return hipSuccess;
+  const dim3 grid(n_multi * p.G), block(256);
   if (D == 128) combine_kernel<128><<<grid, block, 0, s>>>(p);
   else if (D == 64) combine_kernel<64><<<grid, block, 0, s>>>(p);
   else return hipErrorInvalidValue;

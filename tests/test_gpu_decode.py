@@ -164,7 +164,7 @@ def test_error_paths():
     arena.set_lengths([302, 1])
     kn = torch.zeros((1, 2, 128), dtype=torch.bfloat16, device=arena.device)
     with pytest.raises(B.BaklavaError) as e:           # cache 0 is full
-        arena.append(0, kn, kn, 5)
+        arena.append(0, 1, kn, kn, 5)
     assert e.value.status == B.ECAPACITY
     assert arena.lengths().tolist() == [302, 1]
     with pytest.raises(B.BaklavaError) as e:
@@ -174,4 +174,41 @@ def test_error_paths():
     assert arena.lengths().tolist() == [0, 0]
     torch.cuda.synchronize()
     assert arena.len.cpu().tolist() == [0, 0]
+    arena.close()
+
+
+@pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+def test_fused_append_at_item_boundaries(kernel):
+    """baklava_append_decode_attn with the new row landing first / last in a work item, in a new
+    work item of its own, and in an empty cache; the result must equal append followed by
+    attention, and the oracle."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="fusedb", L=1, Hq=8, Hkv=2, batch=4, seed=41, slack=600)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = [500, 300]
+    arena = H.make_arena(w, budgets)
+    arena.set_option(B.OPT_KERNEL, kernel)
+    arena.set_option(B.OPT_CHUNK_TOKENS, 256)
+    lens = [0, 255, 256, 257, 511, 512, 513, 767]
+    st = H.fill_from_host(arena, w, lens, rng)
+    for step in range(3):
+        q, q64 = H.make_q(w, rng, 1)
+        knew = synth.payload(rng, (1, w.batch, w.Hkv, w.D), w.dtype)
+        vnew = synth.payload(rng, (1, w.batch, w.Hkv, w.D), w.dtype)
+        outd = torch.full((1, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=arena.device)
+        arena.append_decode_attn(0, 1, H.to_device_storage(knew, w.dtype, arena.device),
+                                 H.to_device_storage(vnew, w.dtype, arena.device), 900 + step,
+                                 H.to_device_storage(q, w.dtype, arena.device), outd)
+        torch.cuda.synchronize()
+        out = outd.cpu().numpy().astype(np.float64)
+        post = H.download(arena, w)
+        assert arena.lengths().tolist() == [n + step + 1 for n in lens]
+        assert arena.len.cpu().tolist() == arena.lengths().tolist()
+        for c in range(arena.n_caches):
+            b, h = divmod(c, w.Hkv)
+            assert np.array_equal(post.K[c][:-1], st.K[c]) and np.array_equal(post.V[c][:-1], st.V[c])
+            assert np.array_equal(post.K[c][-1], knew[0, b, h]) and np.array_equal(post.V[c][-1], vnew[0, b, h])
+            assert post.pos[c][-1] == 900 + step and post.score[c][-1] == 0.0
+        H.check_decode_against_oracle(arena, w, post, q64, out)
+        st = post
     arena.close()

@@ -24,8 +24,9 @@ def _h():
 
 
 @pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("base,Hq,Hkv", [("long", 8, 2), ("qwen", 7, 1)])
-def test_multi_step_with_kernel_updated_scores(kernel, base, Hq, Hkv):
+def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv):
     H = _h()
     w = synth.shrink(synth.WORKLOADS[base], name="steps", L=2, Hq=Hq, Hkv=Hkv, batch=2, ctx=2048, lo=96,
                      hi=2048, interval=8, slack=8, sink=4, recent=16, steps=20, floor_frac=0.0)
@@ -48,9 +49,17 @@ def test_multi_step_with_kernel_updated_scores(kernel, base, Hq, Hkv):
         kd = H.to_device_storage(knew, w.dtype, arena.device)
         vd = H.to_device_storage(vnew, w.dtype, arena.device)
         token_pos = 100000 + t
-        for l in range(w.L):
-            arena.append(l, kd[l], vd[l], token_pos)
-        out = H.gpu_decode(arena, w, q)
+        if fused:
+            # one launch per layer: the new row joins each cache inside the attention kernel
+            qd = H.to_device_storage(q, w.dtype, arena.device)
+            outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=arena.device)
+            for l in range(w.L):
+                arena.append_decode_attn(l, 1, kd[l], vd[l], token_pos, qd[l], outd[l])
+            torch.cuda.synchronize()
+            out = outd.cpu().numpy().astype(np.float64)
+        else:
+            arena.append(0, w.L, kd, vd, token_pos)
+            out = H.gpu_decode(arena, w, q)
         post = H.download(arena, w)
         k64 = synth.storage_to_f64(knew, w.dtype)
         v64 = synth.storage_to_f64(vnew, w.dtype)
@@ -106,7 +115,7 @@ def test_scores_sum_to_G_per_step_without_eviction():
         for t in range(1, 6):
             q, _ = H.make_q(w, rng, 1)
             kn = H.to_device_storage(synth.payload(rng, (1, 2, w.D), w.dtype), w.dtype, arena.device)
-            arena.append(0, kn, kn, t)
+            arena.append(0, 1, kn, kn, t)
             H.gpu_decode(arena, w, q)
             st = H.download(arena, w)
             for c in range(2):
@@ -134,9 +143,12 @@ def test_free_running_fp64_oracle_on_a_small_replica():
         q, q64 = H.make_q(w, rng, w.L)
         knew = synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype)
         vnew = synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype)
-        arena.append(0, H.to_device_storage(knew[0], w.dtype, arena.device),
-                     H.to_device_storage(vnew[0], w.dtype, arena.device), t)
-        out = H.gpu_decode(arena, w, q)
+        qd = H.to_device_storage(q, w.dtype, arena.device)
+        outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=arena.device)
+        arena.append_decode_attn(0, 1, H.to_device_storage(knew, w.dtype, arena.device),
+                                 H.to_device_storage(vnew, w.dtype, arena.device), t, qd, outd)
+        torch.cuda.synchronize()
+        out = outd.cpu().numpy().astype(np.float64)
         k64, v64 = synth.storage_to_f64(knew, w.dtype), synth.storage_to_f64(vnew, w.dtype)
         do_compact = t % w.interval == 0
         kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=arena.device)

@@ -39,29 +39,6 @@ def parse_args():
     return ap.parse_args()
 
 
-def fill_arena_on_device(arena, w, torch):
-    """Seeded N(0,1) payload rounded to bf16, generated on the device in slabs."""
-    g = torch.Generator(device=arena.device)
-    g.manual_seed(w.seed)
-    slab = 1 << 22  # rows
-    for plane in (arena.k, arena.v):
-        for r0 in range(0, arena.total_tokens, slab):
-            r1 = min(arena.total_tokens, r0 + slab)
-            x = torch.randn((r1 - r0, w.D), generator=g, device=arena.device, dtype=torch.float32)
-            plane[r0:r1].copy_(x)
-            del x
-    if w.scores == "uniform":
-        arena.score.copy_(torch.rand((arena.total_tokens,), generator=g, device=arena.device, dtype=torch.float32))
-    else:
-        arena.score.zero_()
-    # original positions: 0..n-1 inside each cache
-    off = torch.from_numpy(arena.off_host).to(arena.device)
-    cap = torch.from_numpy(arena.cap_host).to(arena.device).to(torch.int64)
-    starts = torch.repeat_interleave(off, cap)
-    arena.pos.copy_((torch.arange(arena.total_tokens, device=arena.device) - starts).to(torch.int32))
-    return g
-
-
 def cpu_baseline(arena, w, q_dev, torch, target_seconds):
     """The fp64 oracle's decode attention timed on this machine's host cores over a bounded sample of
     the same caches (layer 0 first, then further layers until the time target is met)."""
@@ -157,7 +134,7 @@ def main():
     track = w.scores == "kernel"
     arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack, w.sink, w.recent,
                     B.POLICY_SCORE, track)
-    gen = fill_arena_on_device(arena, w, torch)
+    gen = synth.fill_arena_on_device(arena, w)
     cpl = w.batch * w.Hkv
     lens0 = np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], dtype=np.int32)
     lens0 = np.minimum(lens0, w.ctx)
@@ -166,6 +143,7 @@ def main():
         arena.set_option(B.OPT_KERNEL, args.kernel)
     if args.chunk:
         arena.set_option(B.OPT_CHUNK_TOKENS, args.chunk)
+        arena.set_option(B.OPT_CHUNK_TOKENS_WHOLE, args.chunk)
 
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     q = torch.randn((w.L, w.batch, w.Hq, w.D), generator=gen, device=arena.device, dtype=torch.float32).to(tdt)

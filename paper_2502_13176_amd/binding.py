@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(HERE, "libbaklava.so")
 OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
 BF16, F32 = 0, 1
 POLICY_SCORE, POLICY_STREAMING = 0, 1
-OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL = 1, 2, 3
+OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL, OPT_CHUNK_TOKENS_WHOLE = 1, 2, 3, 4
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [

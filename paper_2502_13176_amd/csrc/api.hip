@@ -23,7 +23,8 @@ inline bool hip_ok(hipError_t e) {
 
 constexpr int kMinChunk = 256;
 constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
-constexpr int kDefaultChunk = 512;
+constexpr int kDefaultChunk = 512;        // launches over part of the model (a few hundred MB)
+constexpr int kDefaultChunkWhole = 2048;  // launches over the whole model (GBs): fewer, larger items
 constexpr int kMaxChunk = 1 << 22; // row offsets inside a work item stay below 2^32 bytes
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -35,8 +36,9 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 }
 
 struct WorkspacePlan {
-  size_t items, cib, part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, iorder_all,
-      iorder_layer, multi_all, multi_layer, total;
+  // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
+  size_t items[2], cib[2], iorder[2], multi[2];
+  size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, total;
   int64_t max_items;
 };
 
@@ -63,8 +65,12 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
   for (int64_t c = 0; c < n_caches; ++c) total_tokens += cap[c];
   w.max_items = count_items(cap, n_caches, kSizingChunk);
   size_t o = 0;
-  w.items = o;        o = align256(o + (size_t)w.max_items * sizeof(Item));
-  w.cib = o;          o = align256(o + (size_t)(n_caches + 1) * 4);
+  for (int k = 0; k < 2; ++k) {
+    w.items[k] = o;   o = align256(o + (size_t)w.max_items * sizeof(Item));
+    w.cib[k] = o;     o = align256(o + (size_t)(n_caches + 1) * 4);
+    w.iorder[k] = o;  o = align256(o + (size_t)w.max_items * 4);
+    w.multi[k] = o;   o = align256(o + (size_t)n_caches * 4);
+  }
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
   w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
   w.final_ml = o;     o = align256(o + (size_t)n_caches * G * 2 * 4);
@@ -73,10 +79,6 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
   w.info = o;         o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
   w.order_all = o;    o = align256(o + (size_t)n_caches * 4);
   w.order_layer = o;  o = align256(o + (size_t)n_caches * 4);
-  w.iorder_all = o;   o = align256(o + (size_t)w.max_items * 4);
-  w.iorder_layer = o; o = align256(o + (size_t)w.max_items * 4);
-  w.multi_all = o;    o = align256(o + (size_t)n_caches * 4);
-  w.multi_layer = o;  o = align256(o + (size_t)n_caches * 4);
   w.total = o;
   return w;
 }
@@ -92,12 +94,12 @@ struct baklava_ctx {
   std::vector<int64_t> off;
   std::vector<int32_t> cap, len, budget;
   std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
-  int32_t chunk;
   int32_t kernel_pref;
-  std::vector<int32_t> cib;  // cache -> first item
-  std::vector<int32_t> multi_begin;  // layer -> first entry of the per-layer list of multi-item caches
-  int32_t n_multi;
-  int64_t n_items;
+  struct Schedule {
+    int32_t chunk = 0;
+    std::vector<int32_t> cib;          // cache -> first item
+    std::vector<int32_t> multi_begin;  // layer -> first entry of the list of multi-item caches
+  } sched[2];                          // 0: layer sub-range launches, 1: whole-model launches
   WorkspacePlan plan;
   char* ws;
   bool time_kernel;
@@ -109,9 +111,10 @@ namespace {
 
 // Cuts every cache into runs of `chunk` rows over its whole capacity.  The table depends on the
 // capacities only, so it is uploaded once; the kernels clamp each run to the live length.
-// Two launch orders are kept, both with the items of long caches first: one over the whole
-// model, one inside each layer so that a layer range is a contiguous slice.
-int build_schedule(baklava_ctx* ctx, int chunk) {
+// Schedule 0 serves launches over a layer sub-range: items are ordered layer by layer, inside a
+// layer long caches first, so a layer range is a contiguous slice.  Schedule 1 serves launches
+// over the whole model: long caches first over all layers.
+int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   std::vector<Item> items;
   std::vector<int32_t> cib(ctx->n_caches + 1);
   items.reserve((size_t)count_items(ctx->cap.data(), ctx->n_caches, chunk));
@@ -130,40 +133,28 @@ int build_schedule(baklava_ctx* ctx, int chunk) {
   }
   cib[ctx->n_caches] = (int32_t)items.size();
   if ((int64_t)items.size() > ctx->plan.max_items) return BAKLAVA_ECAPACITY;
-  std::vector<int32_t> io_all, io_layer;
-  io_all.reserve(items.size());
-  io_layer.reserve(items.size());
-  for (int32_t c : ctx->order_all)
-    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) io_all.push_back(i);
-  for (int32_t c : ctx->order_layer)
-    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) io_layer.push_back(i);
-  // Caches with more than one work item need the combine kernel; same two orders.
-  std::vector<int32_t> multi_all, multi_layer, multi_begin(ctx->d.L + 1, 0);
-  for (int32_t c : ctx->order_all)
-    if (cib[c + 1] - cib[c] > 1) multi_all.push_back(c);
-  for (int32_t c : ctx->order_layer) {
-    if (cib[c + 1] - cib[c] > 1) {
-      multi_layer.push_back(c);
+  const std::vector<int32_t>& corder = which == 0 ? ctx->order_layer : ctx->order_all;
+  std::vector<int32_t> iorder, multi, multi_begin(ctx->d.L + 1, 0);
+  iorder.reserve(items.size());
+  for (int32_t c : corder) {
+    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) iorder.push_back(i);
+    if (cib[c + 1] - cib[c] > 1) {  // needs the combine kernel
+      multi.push_back(c);
       multi_begin[c / ctx->cpl + 1] += 1;
     }
   }
   for (int32_t l = 0; l < ctx->d.L; ++l) multi_begin[l + 1] += multi_begin[l];
   if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
   const size_t ni = items.size();
-  if (!multi_all.empty() &&
-      (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi_all, multi_all.data(), multi_all.size() * 4, hipMemcpyHostToDevice)) ||
-       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi_layer, multi_layer.data(), multi_layer.size() * 4, hipMemcpyHostToDevice))))
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items[which], items.data(), ni * sizeof(Item), hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib[which], cib.data(), cib.size() * 4, hipMemcpyHostToDevice)) ||
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder[which], iorder.data(), ni * 4, hipMemcpyHostToDevice)) ||
+      (!multi.empty() &&
+       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi[which], multi.data(), multi.size() * 4, hipMemcpyHostToDevice))))
     return BAKLAVA_EHIP;
-  ctx->multi_begin.swap(multi_begin);
-  ctx->n_multi = (int32_t)multi_all.size();
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items, items.data(), ni * sizeof(Item), hipMemcpyHostToDevice)) ||
-      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib, cib.data(), cib.size() * 4, hipMemcpyHostToDevice)) ||
-      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder_all, io_all.data(), ni * 4, hipMemcpyHostToDevice)) ||
-      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder_layer, io_layer.data(), ni * 4, hipMemcpyHostToDevice)))
-    return BAKLAVA_EHIP;
-  ctx->cib.swap(cib);
-  ctx->n_items = (int64_t)ni;
-  ctx->chunk = chunk;
+  ctx->sched[which].cib.swap(cib);
+  ctx->sched[which].multi_begin.swap(multi_begin);
+  ctx->sched[which].chunk = chunk;
   return BAKLAVA_OK;
 }
 
@@ -180,25 +171,25 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
     if (fused && ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
     if (!fused && ctx->len[c] <= 0) return BAKLAVA_ESTATE;
   }
-  const int32_t i0 = ctx->cib[c0], i1 = ctx->cib[c1];
   const bool whole = layer_begin == 0 && layer_count == ctx->d.L;
+  const int which = whole ? 1 : 0;
+  const baklava_ctx::Schedule& sc = ctx->sched[which];
+  const int32_t i0 = sc.cib[c0], i1 = sc.cib[c1];
   DecodeParams p;
   p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
   p.off = ctx->d.off; p.len = ctx->d.len;
-  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items);
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]);
   // Items are numbered cache by cache, so a layer range is the slice [i0, i1) of the per-layer order.
-  p.order = whole ? reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder_all)
-                  : reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder_layer) + i0;
-  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib);
+  p.order = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder[which]) + i0;
+  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib[which]);
   p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
   p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
   p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
   p.score = ctx->d.score;
   p.pos = ctx->d.pos;
-  const int32_t m0 = ctx->multi_begin[layer_begin], m1 = ctx->multi_begin[layer_begin + layer_count];
-  p.multi = whole ? reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi_all)
-                  : reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi_layer) + m0;
+  const int32_t m0 = sc.multi_begin[layer_begin], m1 = sc.multi_begin[layer_begin + layer_count];
+  p.multi = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi[which]) + m0;
   p.k_new = k_new; p.v_new = v_new;
   p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
   p.cache_begin = (int32_t)c0;
@@ -301,7 +292,8 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
     delete ctx;
     return BAKLAVA_EHIP;
   }
-  int st = build_schedule(ctx, kDefaultChunk);
+  int st = build_schedule(ctx, 0, kDefaultChunk);
+  if (st == BAKLAVA_OK) st = build_schedule(ctx, 1, kDefaultChunkWhole);
   if (st != BAKLAVA_OK) { delete ctx; return st; }
   *out = ctx;
   return BAKLAVA_OK;
@@ -318,9 +310,12 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
   if (!ctx) return BAKLAVA_EINVAL;
   switch (option) {
     case BAKLAVA_OPT_CHUNK_TOKENS:
+    case BAKLAVA_OPT_CHUNK_TOKENS_WHOLE: {
       if (value < kMinChunk || value % 64 || value > kMaxChunk) return BAKLAVA_EINVAL;
-      if ((int32_t)value == ctx->chunk) return BAKLAVA_OK;
-      return build_schedule(ctx, (int32_t)value);
+      const int which = option == BAKLAVA_OPT_CHUNK_TOKENS ? 0 : 1;
+      if ((int32_t)value == ctx->sched[which].chunk) return BAKLAVA_OK;
+      return build_schedule(ctx, which, (int32_t)value);
+    }
     case BAKLAVA_OPT_KERNEL:
       if (value < 0 || value > 2) return BAKLAVA_EINVAL;
       if (value == 2 && !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_EINVAL;

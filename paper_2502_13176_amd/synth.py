@@ -174,3 +174,29 @@ def storage_to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
 
 def uniform_scores(rng: np.random.Generator, n: int) -> np.ndarray:
     return rng.random(n, dtype=np.float32)
+
+
+def fill_arena_on_device(arena, w: Workload):
+    """Fills the K/V/score/pos planes of a device arena (an object with torch tensors k, v, score,
+    pos and numpy tables off_host, cap_host) with the seeded payload, generated on the device in
+    slabs: N(0,1) rounded to the storage type, scores U(0,1) or zero, pos = row index inside its
+    cache.  Returns the torch generator so that further inputs continue the same stream."""
+    import torch
+    g = torch.Generator(device=arena.device)
+    g.manual_seed(w.seed)
+    slab = 1 << 22  # rows
+    for plane in (arena.k, arena.v):
+        for r0 in range(0, arena.total_tokens, slab):
+            r1 = min(arena.total_tokens, r0 + slab)
+            x = torch.randn((r1 - r0, w.D), generator=g, device=arena.device, dtype=torch.float32)
+            plane[r0:r1].copy_(x)
+            del x
+    if w.scores == "uniform":
+        arena.score.copy_(torch.rand((arena.total_tokens,), generator=g, device=arena.device, dtype=torch.float32))
+    else:
+        arena.score.zero_()
+    off = torch.from_numpy(arena.off_host).to(arena.device)
+    cap = torch.from_numpy(arena.cap_host).to(arena.device).to(torch.int64)
+    starts = torch.repeat_interleave(off, cap)
+    arena.pos.copy_((torch.arange(arena.total_tokens, device=arena.device) - starts).to(torch.int32))
+    return g

@@ -142,3 +142,9 @@ def check_decode_against_oracle(arena, w, st: HostState, q64: np.ndarray, out_gp
         assert err <= tol, f"cache {c} (n={st.K[c].shape[0]}): max-abs error {err:.3e} > {tol}"
         worst = max(worst, err)
     return worst
+
+
+def set_chunk(arena: B.Arena, chunk: int) -> None:
+    """Rows per split-K work item, for both kinds of launch (layer sub-range and whole model)."""
+    arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+    arena.set_option(B.OPT_CHUNK_TOKENS_WHOLE, chunk)

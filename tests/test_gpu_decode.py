@@ -46,7 +46,7 @@ def test_llama_single_layer_at_full_size(kernel, chunk):
     budgets = synth.budgets_for(w, B.alloc_proportional)
     arena = H.make_arena(w, budgets)
     arena.set_option(B.OPT_KERNEL, kernel)
-    arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+    H.set_chunk(arena, chunk)
     lens = [budgets[c % w.Hkv] for c in range(arena.n_caches)]
     st = H.fill_from_host(arena, w, lens, rng)
     q, q64 = H.make_q(w, rng, w.L)
@@ -79,7 +79,7 @@ def test_ragged_lengths_all_shapes(dtype, D, Hq, Hkv):
     for kernel in _kernels_for(w):
         arena.set_option(B.OPT_KERNEL, kernel)
         for chunk in (256, 512, 4096):
-            arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+            H.set_chunk(arena, chunk)
             out = H.gpu_decode(arena, w, q)
             H.check_decode_against_oracle(arena, w, st, q64, out)
         # second layer alone
@@ -101,7 +101,7 @@ def test_result_does_not_depend_on_split_factor(kernel):
     q, q64 = H.make_q(w, rng, w.L)
     outs = []
     for chunk in (8192, 3584, 1024, 256):      # 1, 2, 7 and 28 splits of the long cache
-        arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
+        H.set_chunk(arena, chunk)
         outs.append(H.gpu_decode(arena, w, q))
         H.check_decode_against_oracle(arena, w, st, q64, outs[-1])
     for o in outs[1:]:
@@ -168,7 +168,7 @@ def test_error_paths():
     assert e.value.status == B.ECAPACITY
     assert arena.lengths().tolist() == [302, 1]
     with pytest.raises(B.BaklavaError) as e:
-        arena.set_option(B.OPT_CHUNK_TOKENS, 100)
+        H.set_chunk(arena, 100)
     assert e.value.status == B.EINVAL
     arena.reset()
     assert arena.lengths().tolist() == [0, 0]
@@ -188,7 +188,7 @@ def test_fused_append_at_item_boundaries(kernel):
     budgets = [500, 300]
     arena = H.make_arena(w, budgets)
     arena.set_option(B.OPT_KERNEL, kernel)
-    arena.set_option(B.OPT_CHUNK_TOKENS, 256)
+    H.set_chunk(arena, 256)
     lens = [0, 255, 256, 257, 511, 512, 513, 767]
     st = H.fill_from_host(arena, w, lens, rng)
     for step in range(3):

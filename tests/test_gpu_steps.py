@@ -35,7 +35,7 @@ def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv):
     assert budgets == synth.budgets_for(w, O.alloc_proportional)
     arena = H.make_arena(w, budgets, track=True)
     arena.set_option(B.OPT_KERNEL, kernel)
-    arena.set_option(B.OPT_CHUNK_TOKENS, 256)
+    H.set_chunk(arena, 256)
     cpl = w.batch * w.Hkv
     lens = [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]
     H.fill_from_host(arena, w, lens, rng, scores="zero")
@@ -110,7 +110,7 @@ def test_scores_sum_to_G_per_step_without_eviction():
     for kernel in (B.KERNEL_VALU, B.KERNEL_MFMA):
         arena = H.make_arena(w, budgets, track=True)
         arena.set_option(B.OPT_KERNEL, kernel)
-        arena.set_option(B.OPT_CHUNK_TOKENS, 512)
+        H.set_chunk(arena, 512)
         H.fill_from_host(arena, w, budgets, rng, scores="zero")
         for t in range(1, 6):
             q, _ = H.make_q(w, rng, 1)

@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
+    ap.add_argument("--no-other-mode", action="store_true",
+                    help="skip the extra region in the other launch mode (keeps profiler traces to one mode)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle leg")
     return ap.parse_args()
 
@@ -197,7 +199,7 @@ def main():
     roof_r = region(min(args.steps, 64), args.mode, time_kernel=True)
     # Upper bound for comparison: all layers in one launch.
     other = "stack" if args.mode == "layer" else "layer"
-    other_r = region(min(args.steps, 32), other, time_kernel=False)
+    other_r = None if args.no_other_mode else region(min(args.steps, 32), other, time_kernel=False)
 
     elapsed = main_r["elapsed"]
     ms_per_step = elapsed * 1e3 / args.steps
@@ -231,12 +233,13 @@ def main():
             "algorithmic_bytes_per_launch": int(avg_launch_bytes),
         },
     }
-    result["other_launch_mode"] = {
-        "launch_mode": other, "steps": other_r["steps"],
-        "value": round(other_r["kv_bytes"] / other_r["elapsed"] / 1e9, 2), "unit": "GB/s",
-        "us_per_step": round(other_r["elapsed"] * 1e6 / other_r["steps"], 1),
-        "pct_of_hbm_peak": round(100.0 * other_r["kv_bytes"] / other_r["elapsed"] / 1e9 / HBM_PEAK_GBPS, 2),
-    }
+    if other_r is not None:
+      result["other_launch_mode"] = {
+          "launch_mode": other, "steps": other_r["steps"],
+          "value": round(other_r["kv_bytes"] / other_r["elapsed"] / 1e9, 2), "unit": "GB/s",
+          "us_per_step": round(other_r["elapsed"] * 1e6 / other_r["steps"], 1),
+          "pct_of_hbm_peak": round(100.0 * other_r["kv_bytes"] / other_r["elapsed"] / 1e9 / HBM_PEAK_GBPS, 2),
+      }
     result["stream_probe"] = stream_probe(torch, B, arena.device)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)

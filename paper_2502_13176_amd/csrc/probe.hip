@@ -2,8 +2,8 @@
 // calibrate the HBM byte counters (what FETCH_SIZE / WRITE_SIZE read for a known transfer) and
 // give the bandwidth a trivial kernel reaches on the same device.
 //
-// Each workgroup owns one contiguous 256 KiB block and keeps 8 16-byte loads per thread in
-// flight, the access shape that gave the highest read bandwidth of the shapes tried.
+// The read sweep gives each workgroup one contiguous 256 KiB block and keeps 8 16-byte loads per
+// thread in flight, the access shape that gave the highest read bandwidth of the shapes tried.
 #include "common.h"
 
 namespace baklava {
@@ -13,19 +13,11 @@ namespace {
 constexpr int kBlock16 = 16384;  // 16-byte pieces per workgroup block (256 KiB)
 constexpr int kU = 8;
 
+// Plain grid-stride copy, one 16-byte piece per thread and iteration.
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ dst,
                                                           const uint4* __restrict__ src, int64_t n16) {
-  const int64_t b0 = (int64_t)blockIdx.x * kBlock16;
-  const int64_t b1 = min(b0 + kBlock16, n16);
-  for (int64_t i = b0 + threadIdx.x; i < b1; i += 256 * kU) {
-    uint4 v[kU];
-#pragma unroll
-    for (int u = 0; u < kU; ++u)
-      if (i + u * 256 < b1) v[u] = src[i + u * 256];
-#pragma unroll
-    for (int u = 0; u < kU; ++u)
-      if (i + u * 256 < b1) dst[i + u * 256] = v[u];
-  }
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
 __global__ __launch_bounds__(256) void stream_read_kernel(uint32_t* __restrict__ dst,
@@ -51,7 +43,7 @@ hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mo
   if (n16 <= 0) return hipSuccess;
   const dim3 grid((unsigned)((n16 + kBlock16 - 1) / kBlock16)), block(256);
   if (mode == 0)
-    stream_copy_kernel<<<grid, block, 0, s>>>(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
+    stream_copy_kernel<<<dim3(4096), block, 0, s>>>(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
   else
     stream_read_kernel<<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
   return hipGetLastError();

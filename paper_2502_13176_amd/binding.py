@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libbaklava.so")
+# BAKLAVA_LIB lets a tuning run load a differently built copy of the same library.
+LIB_PATH = os.environ.get("BAKLAVA_LIB") or os.path.join(HERE, "libbaklava.so")
 
 OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
 BF16, F32 = 0, 1

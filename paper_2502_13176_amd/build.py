@@ -21,13 +21,13 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = True) -> str:
+def build_library(verbose: bool = True, out_path: str = LIB_PATH, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for s in SOURCES:
         path = os.path.join(CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".hip") else ["-x", "hip", path])
-    cmd += ["-o", LIB_PATH]
+    cmd += ["-o", out_path]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -37,7 +37,7 @@ def build_library(verbose: bool = True) -> str:
         print(out)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

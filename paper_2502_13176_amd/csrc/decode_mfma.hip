@@ -31,8 +31,8 @@ typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kSlab = 32;       // rows per wavefront iteration
-constexpr int kVStride = 264;   // bytes between staged V rows: 66 dwords, so the 4 row groups of a
-                                // transposed read fall into disjoint LDS banks
+constexpr int kVStride = 288;   // bytes between staged V rows: 256 + 32, so the 16 rows touched by one
+                                // transposed read spread evenly over the LDS banks
 constexpr int kD = 128;
 constexpr float kNegInf = -__builtin_huge_valf();
 
@@ -40,10 +40,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_cast(bf16x8_t, x); }
 
-__global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
+#ifndef BAKLAVA_MFMA_WAVES_PER_EU
+#define BAKLAVA_MFMA_WAVES_PER_EU 3
+#endif
+__global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
 
   const Item it = p.items[p.order[blockIdx.x]];
@@ -123,9 +127,7 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
     // ---- stage V rows in LDS, then the next slab's V loads reuse the registers ----------------
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      unsigned char* dst = myl + (jg + 4 * i) * kVStride + n16 * 16;
-      *reinterpret_cast<u32x2_t*>(dst) = u32x2_t{vr[i].x, vr[i].y};
-      *reinterpret_cast<u32x2_t*>(dst + 8) = u32x2_t{vr[i].z, vr[i].w};
+      *reinterpret_cast<u32x4_t*>(myl + (jg + 4 * i) * kVStride + n16 * 16) = vr[i];
     }
     BAKLAVA_LOAD_V(tn)
 
@@ -180,18 +182,18 @@ __global__ __launch_bounds__(256) void decode_partial_mfma(DecodeParams p) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ds_read_b64_tr_b16 hands lane 4a+j of a 16-lane group the j-th 16-bit element of the four
+    // lanes 4k+a (k = 0..3).  Lane 4k+a points at row 4*jg+k of the tile, head-dim elements
+    // 16b+4a .. +3, so lane m receives V[row 4*jg+k][16b+m] for k = 0..3: one half of the A operand.
+    const unsigned char* tr0 = myl + (jg * 4 + (n16 >> 2)) * kVStride + (n16 & 3) * 8;
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-      u32x4_t a;
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        const int r0 = (e / 4) * 16 + jg * 4 + (e % 4);
-        const uint32_t lo = *reinterpret_cast<const uint16_t*>(myl + r0 * kVStride + (b * 16 + n16) * 2);
-        const uint32_t hi = *reinterpret_cast<const uint16_t*>(myl + (r0 + 1) * kVStride + (b * 16 + n16) * 2);
-        a[e / 2] = lo | (hi << 16);
-      }
-      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(ph), o[b], 0, 0, 0);
-      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), pl, o[b], 0, 0, 0);
+      typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + b * 32));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + 16 * kVStride + b * 32));
+      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph), o[b], 0, 0, 0);
+      o[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl, o[b], 0, 0, 0);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();

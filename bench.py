@@ -240,6 +240,23 @@ def main():
           "us_per_step": round(other_r["elapsed"] * 1e6 / other_r["steps"], 1),
           "pct_of_hbm_peak": round(100.0 * other_r["kv_bytes"] / other_r["elapsed"] / 1e9 / HBM_PEAK_GBPS, 2),
       }
+    if not args.no_compaction:
+        # One eviction in which nearly every row moves: all caches full, fresh random scores.
+        arena.set_lengths(arena.cap_host)
+        arena.score.copy_(torch.rand((arena.total_tokens,), generator=gen, device=arena.device, dtype=torch.float32))
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        arena.compact(0, w.L)
+        e1.record()
+        torch.cuda.synchronize()
+        kept_bytes = int(arena.lengths().astype(np.int64).sum()) * w.token_bytes
+        ms = e0.elapsed_time(e1)
+        result["full_eviction"] = {
+            "us": round(ms * 1e3, 1), "kept_kv_bytes": kept_bytes,
+            "moved_GBps_read_plus_write": round(2 * kept_bytes / ms / 1e6, 1),
+            "note": "every cache at capacity, fresh U(0,1) scores: nearly every kept row moves",
+        }
     result["stream_probe"] = stream_probe(torch, B, arena.device)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)

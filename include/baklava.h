@@ -118,10 +118,12 @@ typedef struct {
 
 /*
  * Bytes of device workspace a context with this description needs (split partials, work-item
- * table, kept-index lists, and the logit stash when track_scores is set).  Pointer fields of
- * `desc` are ignored.  cap_host HOST [n_caches].  Returns 0 on invalid arguments.
+ * tables, kept-index lists, halo rows of the eviction move, and the logit stash when
+ * track_scores is set).  Pointer fields of `desc` are ignored.  cap_host HOST [n_caches],
+ * budget_host HOST [L*Hkv].  Returns 0 on invalid arguments.
  */
-size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host);
+size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host,
+                               const int32_t* budget_host);
 
 /*
  * Creates a context.  The *_host arrays are copies of the device tables in `desc` (the library

@@ -69,7 +69,7 @@ def lib() -> C.CDLL:
     L.baklava_alloc_threshold.argtypes = [f64p, C.c_int32, i32p, C.c_double, C.c_double, i32p]
     L.baklava_layout.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i64p, i32p, i64p]
     L.baklava_workspace_bytes.restype = C.c_size_t
-    L.baklava_workspace_bytes.argtypes = [C.POINTER(Desc), i32p]
+    L.baklava_workspace_bytes.argtypes = [C.POINTER(Desc), i32p, i32p]
     L.baklava_create.argtypes = [C.POINTER(Desc), i64p, i32p, i32p, i32p, C.POINTER(C.c_void_p)]
     L.baklava_destroy.argtypes = [C.c_void_p]
     L.baklava_set_option.argtypes = [C.c_void_p, C.c_int32, C.c_int64]
@@ -183,7 +183,8 @@ class Arena:
         d.L, d.Hq, d.Hkv, d.D, d.batch = L, Hq, Hkv, D, batch
         d.dtype = BF16 if dtype == "bf16" else F32
         d.sink, d.recent, d.policy, d.track_scores = sink, recent, policy, int(bool(track_scores))
-        ws_bytes = lib().baklava_workspace_bytes(C.byref(d), _p(self.cap_host, C.c_int32))
+        ws_bytes = lib().baklava_workspace_bytes(C.byref(d), _p(self.cap_host, C.c_int32),
+                                                 _p(self.budget_host, C.c_int32))
         if ws_bytes == 0:
             raise BaklavaError(EINVAL, "baklava_workspace_bytes")
         self.workspace = torch.zeros((ws_bytes,), dtype=torch.uint8, device=dev)

@@ -38,7 +38,9 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
   size_t items[2], cib[2], iorder[2], multi[2];
-  size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer, total;
+  size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer;
+  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, total;
+  int64_t n_segs, halo_rows;
   int64_t max_items;
 };
 
@@ -57,12 +59,30 @@ bool shape_ok(const baklava_desc* d) {
   return true;
 }
 
-WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
+// Segments of the eviction move: the destination range [0, budget) of every cache in runs of
+// kMoveSegRows rows; a segment that has a successor owns a halo slot of cap - budget rows.
+void count_segments(const baklava_desc* d, const int32_t* cap, const int32_t* budget, int64_t* n_segs,
+                    int64_t* halo_rows) {
+  const int64_t cpl = (int64_t)d->batch * d->Hkv;
+  const int64_t n_caches = (int64_t)d->L * cpl;
+  *n_segs = 0;
+  *halo_rows = 0;
+  for (int64_t c = 0; c < n_caches; ++c) {
+    const int64_t b = budget[(c / cpl) * d->Hkv + c % d->Hkv];
+    const int64_t ns = std::max<int64_t>(1, (b + kMoveSegRows - 1) / kMoveSegRows);
+    *n_segs += ns;
+    *halo_rows += (ns - 1) * std::max<int64_t>(0, cap[c] - b);
+  }
+}
+
+WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const int32_t* budget) {
   WorkspacePlan w{};
   const int64_t n_caches = (int64_t)d->L * d->batch * d->Hkv;
   const int G = d->Hq / d->Hkv;
+  const size_t row_bytes = (size_t)d->D * (d->dtype == BAKLAVA_BF16 ? 2 : 4);
   int64_t total_tokens = 0;
   for (int64_t c = 0; c < n_caches; ++c) total_tokens += cap[c];
+  count_segments(d, cap, budget, &w.n_segs, &w.halo_rows);
   w.max_items = count_items(cap, n_caches, kSizingChunk);
   size_t o = 0;
   for (int k = 0; k < 2; ++k) {
@@ -79,6 +99,12 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap) {
   w.info = o;         o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
   w.order_all = o;    o = align256(o + (size_t)n_caches * 4);
   w.order_layer = o;  o = align256(o + (size_t)n_caches * 4);
+  w.segs = o;         o = align256(o + (size_t)w.n_segs * sizeof(MoveSeg));
+  w.seg_split = o;    o = align256(o + (size_t)w.n_segs * 4);
+  w.halo_k = o;       o = align256(o + (size_t)w.halo_rows * row_bytes);
+  w.halo_v = o;       o = align256(o + (size_t)w.halo_rows * row_bytes);
+  w.halo_score = o;   o = align256(o + (size_t)w.halo_rows * 4);
+  w.halo_pos = o;     o = align256(o + (size_t)w.halo_rows * 4);
   w.total = o;
   return w;
 }
@@ -94,6 +120,7 @@ struct baklava_ctx {
   std::vector<int64_t> off;
   std::vector<int32_t> cap, len, budget;
   std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
+  std::vector<int32_t> seg_begin;               // cache -> first segment of the eviction move
   int32_t kernel_pref;
   struct Schedule {
     int32_t chunk = 0;
@@ -186,6 +213,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
   p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
   p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
+  p.cap = ctx->d.cap;
   p.score = ctx->d.score;
   p.pos = ctx->d.pos;
   const int32_t m0 = sc.multi_begin[layer_begin], m1 = sc.multi_begin[layer_begin + layer_count];
@@ -230,12 +258,15 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
 
 extern "C" int baklava_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host) {
-  if (!shape_ok(desc) || !cap_host) return 0;
+extern "C" size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host,
+                                          const int32_t* budget_host) {
+  if (!shape_ok(desc) || !cap_host || !budget_host) return 0;
   const int64_t n_caches = (int64_t)desc->L * desc->batch * desc->Hkv;
   for (int64_t c = 0; c < n_caches; ++c)
     if (cap_host[c] < 0) return 0;
-  return plan_workspace(desc, cap_host).total;
+  for (int64_t i = 0; i < (int64_t)desc->L * desc->Hkv; ++i)
+    if (budget_host[i] < 0) return 0;
+  return plan_workspace(desc, cap_host, budget_host).total;
 }
 
 extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host, const int32_t* cap_host,
@@ -274,7 +305,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
   ctx->kernel_pref = 0;
   ctx->time_kernel = false;
   ctx->ev_used = 0;
-  ctx->plan = plan_workspace(desc, cap_host);
+  ctx->plan = plan_workspace(desc, cap_host, budget_host);
   ctx->ws = reinterpret_cast<char*>(desc->workspace);
   if (desc->workspace_bytes < ctx->plan.total) { delete ctx; return BAKLAVA_ECAPACITY; }
 
@@ -291,6 +322,34 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_layer, ctx->order_layer.data(), n_caches * 4, hipMemcpyHostToDevice))) {
     delete ctx;
     return BAKLAVA_EHIP;
+  }
+  // Segment table of the eviction move (depends on budgets and capacities only).
+  {
+    std::vector<MoveSeg> segs;
+    segs.reserve((size_t)ctx->plan.n_segs);
+    ctx->seg_begin.assign(n_caches + 1, 0);
+    int64_t halo = 0;
+    for (int64_t c = 0; c < n_caches; ++c) {
+      ctx->seg_begin[c] = (int32_t)segs.size();
+      const int64_t b = ctx->budget[(c / ctx->cpl) * desc->Hkv + c % desc->Hkv];
+      const int64_t hs = std::max<int64_t>(0, ctx->cap[c] - b);
+      const int64_t ns = std::max<int64_t>(1, (b + kMoveSegRows - 1) / kMoveSegRows);
+      for (int64_t k = 0; k < ns; ++k) {
+        MoveSeg sg;
+        sg.c = (int32_t)c;
+        sg.a = (int32_t)(k * kMoveSegRows);
+        sg.halo_row = (k + 1 < ns && hs > 0) ? (int32_t)halo : -1;
+        sg.pad = 0;
+        if (k + 1 < ns) halo += hs;
+        segs.push_back(sg);
+      }
+    }
+    ctx->seg_begin[n_caches] = (int32_t)segs.size();
+    if ((int64_t)segs.size() != ctx->plan.n_segs || halo != ctx->plan.halo_rows || halo > INT32_MAX ||
+        !hip_ok(hipMemcpy(ctx->ws + ctx->plan.segs, segs.data(), segs.size() * sizeof(MoveSeg), hipMemcpyHostToDevice))) {
+      delete ctx;
+      return BAKLAVA_EHIP;
+    }
   }
   int st = build_schedule(ctx, 0, kDefaultChunk);
   if (st == BAKLAVA_OK) st = build_schedule(ctx, 1, kDefaultChunkWhole);
@@ -418,9 +477,17 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
   p.sink = ctx->d.sink; p.recent = ctx->d.recent; p.policy = ctx->d.policy;
   p.row_bytes = ctx->row_bytes;
   p.write_identity = kept_idx_out ? 1 : 0;
+  const int32_t s0 = ctx->seg_begin[c0], s1 = ctx->seg_begin[c1];
+  p.segs = reinterpret_cast<const MoveSeg*>(ctx->ws + ctx->plan.segs) + s0;
+  p.seg_split = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.seg_split);
+  p.seg_base = s0;
+  p.halo_k = ctx->ws + ctx->plan.halo_k;
+  p.halo_v = ctx->ws + ctx->plan.halo_v;
+  p.halo_score = reinterpret_cast<float*>(ctx->ws + ctx->plan.halo_score);
+  p.halo_pos = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.halo_pos);
   hipStream_t s = (hipStream_t)stream;
   if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
-  if (!hip_ok(launch_compact_move(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
+  if (!hip_ok(launch_compact_move(p, s1 - s0, s))) return BAKLAVA_EHIP;
   for (int64_t c = c0; c < c1; ++c) {
     const int32_t b = ctx->budget[(c / ctx->cpl) * ctx->d.Hkv + c % ctx->d.Hkv];
     ctx->len[c] = std::min(ctx->len[c], b);

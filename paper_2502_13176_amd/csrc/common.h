@@ -7,6 +7,8 @@
 
 namespace baklava {
 
+constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move
+
 // One split-K work item: rows [start, start + count) of cache c; its partial result goes to
 // partial slot `slot`.  Rows at or beyond the cache's live length are skipped by the kernel.
 struct Item {
@@ -34,7 +36,9 @@ struct DecodeParams {
   float* part_o;                   // [n_items, G, D] un-normalised partial outputs
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
   float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
-  float* logits;                   // [total_tokens, G] scaled logits in log2 units (track_scores)
+  float* logits;                   // scaled logits in log2 units (track_scores): cache c owns
+                                   // [G * off_c, G * (off_c + cap_c)), query head g at + g * cap_c
+  const int32_t* cap;
   float* score;
   int32_t* pos;
   const int32_t* multi;            // caches of the launched range that have more than one work item
@@ -64,6 +68,14 @@ struct AppendParams {
   int32_t row_bytes;
 };
 
+// One destination segment of the eviction move: rows [a, a + seg_rows) of cache c.  Segments that
+// have a successor own a halo slot (room for cap - budget rows) in the workspace.
+struct MoveSeg {
+  int32_t c, a;
+  int32_t halo_row;  // first row of this segment's halo slot, or -1
+  int32_t pad;
+};
+
 struct CompactParams {
   void* k;
   void* v;
@@ -79,6 +91,13 @@ struct CompactParams {
   int32_t sink, recent, policy;
   int32_t row_bytes;
   int32_t write_identity;  // 1: also write 0..n-1 for caches that evict nothing
+  const MoveSeg* segs;     // segments of the launched cache range
+  int32_t* seg_split;      // [n_segs] first destination row of a segment whose source lies past its end
+  void* halo_k;            // halo copies of the rows a segment needs from beyond its end
+  void* halo_v;
+  float* halo_score;
+  int32_t* halo_pos;
+  int32_t seg_base;        // index of segs[0] in seg_split
 };
 
 // Launchers (defined next to their kernels).  All return hipError_t of the launch.
@@ -89,7 +108,7 @@ hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
 hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s);
-hipError_t launch_compact_move(const CompactParams& p, int n_caches, hipStream_t s);
+hipError_t launch_compact_move(const CompactParams& p, int n_segs, hipStream_t s);
 hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mode, hipStream_t s);
 
 }  // namespace baklava

@@ -1,5 +1,5 @@
-// Budget-enforcing eviction (f_evict, Eqs. 5-6): selection of the surviving rows, then a stable
-// in-place move.  One workgroup per cache; long caches are launched first.
+// Budget-enforcing eviction (f_evict, Eqs. 5-6): selection of the surviving rows (one workgroup
+// per cache, long caches first), then a stable in-place move (one workgroup per segment).
 #include "common.h"
 
 namespace baklava {
@@ -127,57 +127,120 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
 constexpr int kMoveThreads = 512;
 constexpr int kMoveRows = 128;  // rows per tile
 
-// Row p <- row kept[p], p ascending.  kept[p] >= p, so a tile's sources are never rows an
-// earlier tile wrote, and within a tile every load finishes (barrier) before any store.
+// The move is stable and in place: row p <- row kept[p], with kept[p] >= p and
+// kept[p] - p <= (rows evicted) <= capacity - budget.  A cache's destination range is cut into
+// segments of kMoveSegRows rows, one workgroup each.  Inside a segment tiles go in ascending
+// order and every load of a tile finishes (barrier) before any store, so a tile's sources are
+// never rows an earlier tile wrote.  The only rows a segment reads that another segment writes
+// are the few at its end whose source lies past the segment: those are copied to a halo slot
+// by a first kernel, before anything is overwritten.
+
+// Phase 1: save the halo of every segment that has a successor.
+template <int PIECES>
+__global__ __launch_bounds__(256) void compact_halo_kernel(CompactParams p) {
+  const MoveSeg sg = p.segs[blockIdx.x];
+  const CompactInfo info = p.info[sg.c];
+  if (info.first_moved >= info.old_len) return;  // nothing evicted
+  const int b = info.new_len;
+  const int e = sg.a + kMoveSegRows;
+  if (e >= b || sg.halo_row < 0) return;         // last segment: its far sources are overwritten by nobody
+  const int tid = threadIdx.x;
+  const int64_t off = p.off[sg.c];
+  const int32_t* kept = p.kept + off;
+  // first destination row whose source is at or past the segment end (kept is ascending)
+  int lo = sg.a, hi = e;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (kept[mid] >= e) hi = mid; else lo = mid + 1;
+  }
+  const int split = lo, n_halo = e - split;
+  if (tid == 0) p.seg_split[p.seg_base + blockIdx.x] = split;
+  const uint4* K = reinterpret_cast<const uint4*>(p.k) + off * PIECES;
+  const uint4* V = reinterpret_cast<const uint4*>(p.v) + off * PIECES;
+  uint4* HK = reinterpret_cast<uint4*>(p.halo_k) + (int64_t)sg.halo_row * PIECES;
+  uint4* HV = reinterpret_cast<uint4*>(p.halo_v) + (int64_t)sg.halo_row * PIECES;
+  for (int idx = tid; idx < n_halo * PIECES; idx += 256) {
+    const int r = idx / PIECES, piece = idx % PIECES;
+    const int64_t src = kept[split + r];
+    HK[(int64_t)r * PIECES + piece] = K[src * PIECES + piece];
+    HV[(int64_t)r * PIECES + piece] = V[src * PIECES + piece];
+  }
+  for (int r = tid; r < n_halo; r += 256) {
+    const int src = kept[split + r];
+    p.halo_score[sg.halo_row + r] = p.score[off + src];
+    p.halo_pos[sg.halo_row + r] = p.pos[off + src];
+  }
+}
+
+// Phase 2: the move itself.
 template <int PIECES>  // 16-byte pieces per row
 __global__ __launch_bounds__(kMoveThreads) void compact_move_kernel(CompactParams p) {
-  const int c = p.order[blockIdx.x];
+  const MoveSeg sg = p.segs[blockIdx.x];
+  const int c = sg.c;
   const CompactInfo info = p.info[c];
   if (info.first_moved >= info.old_len) return;  // nothing evicted
   const int tid = threadIdx.x;
+  const int b = info.new_len;
+  if (sg.a == 0 && tid == 0) p.len[c] = b;
+  const int e = min(sg.a + kMoveSegRows, b);
+  if (e <= info.first_moved) return;             // every row of this segment stays where it is
+  // rows [split, e) take their source from the halo slot
+  const bool has_halo = (sg.a + kMoveSegRows < b) && sg.halo_row >= 0;
+  const int split = has_halo ? p.seg_split[p.seg_base + blockIdx.x] : e;
   const int64_t off = p.off[c];
   const int32_t* kept = p.kept + off;
-  const int b = info.new_len;
   constexpr int PER_PLANE = kMoveRows * PIECES / kMoveThreads;  // pieces per thread per plane
   uint4* K = reinterpret_cast<uint4*>(p.k) + off * PIECES;
   uint4* V = reinterpret_cast<uint4*>(p.v) + off * PIECES;
+  const uint4* HK = reinterpret_cast<const uint4*>(p.halo_k) + (int64_t)sg.halo_row * PIECES;
+  const uint4* HV = reinterpret_cast<const uint4*>(p.halo_v) + (int64_t)sg.halo_row * PIECES;
   float* score = p.score + off;
   int32_t* pos = p.pos + off;
 
-  const int first = (info.first_moved / kMoveRows) * kMoveRows;
-  for (int p0 = first; p0 < b; p0 += kMoveRows) {
+  const int first = max(sg.a, (info.first_moved / kMoveRows) * kMoveRows);
+  for (int p0 = first; p0 < e; p0 += kMoveRows) {
     uint4 kb[PER_PLANE], vb[PER_PLANE];
     float sc = 0.f;
     int ps = 0;
 #pragma unroll
     for (int i = 0; i < PER_PLANE; ++i) {
       const int idx = tid + i * kMoveThreads;
-      const int row = min(p0 + idx / PIECES, b - 1), piece = idx % PIECES;  // clamped: a live row
-      const int64_t src = kept[row];
-      kb[i] = K[src * PIECES + piece];
-      vb[i] = V[src * PIECES + piece];
+      const int row = min(p0 + idx / PIECES, e - 1), piece = idx % PIECES;  // clamped: a row of this segment
+      if (row >= split) {
+        kb[i] = HK[(int64_t)(row - split) * PIECES + piece];
+        vb[i] = HV[(int64_t)(row - split) * PIECES + piece];
+      } else {
+        const int64_t src = kept[row];
+        kb[i] = K[src * PIECES + piece];
+        vb[i] = V[src * PIECES + piece];
+      }
     }
-    if (tid < kMoveRows && p0 + tid < b) {
-      const int src = kept[p0 + tid];
-      sc = score[src];
-      ps = pos[src];
+    if (tid < kMoveRows && p0 + tid < e) {
+      const int row = p0 + tid;
+      if (row >= split) {
+        sc = p.halo_score[sg.halo_row + row - split];
+        ps = p.halo_pos[sg.halo_row + row - split];
+      } else {
+        const int src = kept[row];
+        sc = score[src];
+        ps = pos[src];
+      }
     }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < PER_PLANE; ++i) {
       const int idx = tid + i * kMoveThreads;
       const int row = p0 + idx / PIECES, piece = idx % PIECES;
-      if (row < b) {
+      if (row < e) {
         K[(int64_t)row * PIECES + piece] = kb[i];
         V[(int64_t)row * PIECES + piece] = vb[i];
       }
     }
-    if (tid < kMoveRows && p0 + tid < b) {
+    if (tid < kMoveRows && p0 + tid < e) {
       score[p0 + tid] = sc;
       pos[p0 + tid] = ps;
     }
   }
-  if (tid == 0) p.len[c] = b;
 }
 
 }  // namespace
@@ -188,13 +251,22 @@ hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream
   return hipGetLastError();
 }
 
-hipError_t launch_compact_move(const CompactParams& p, int n_caches, hipStream_t s) {
-  if (n_caches <= 0) return hipSuccess;
-  const dim3 grid(n_caches), block(kMoveThreads);
+hipError_t launch_compact_move(const CompactParams& p, int n_segs, hipStream_t s) {
+  if (n_segs <= 0) return hipSuccess;
+  const dim3 grid(n_segs);
   switch (p.row_bytes / 16) {
-    case 8: compact_move_kernel<8><<<grid, block, 0, s>>>(p); break;
-    case 16: compact_move_kernel<16><<<grid, block, 0, s>>>(p); break;
-    case 32: compact_move_kernel<32><<<grid, block, 0, s>>>(p); break;
+    case 8:
+      compact_halo_kernel<8><<<grid, dim3(256), 0, s>>>(p);
+      compact_move_kernel<8><<<grid, dim3(kMoveThreads), 0, s>>>(p);
+      break;
+    case 16:
+      compact_halo_kernel<16><<<grid, dim3(256), 0, s>>>(p);
+      compact_move_kernel<16><<<grid, dim3(kMoveThreads), 0, s>>>(p);
+      break;
+    case 32:
+      compact_halo_kernel<32><<<grid, dim3(256), 0, s>>>(p);
+      compact_move_kernel<32><<<grid, dim3(kMoveThreads), 0, s>>>(p);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -105,6 +105,11 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
     vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + off);                                          \
   }
 
+  // Head n16's run of this cache's logit stash, at the item's first row (loaded once, before the
+  // loop: a load inside the loop would make the in-order wait counter stall on the prefetches).
+  float* lg = nullptr;
+  if (p.track && n16 < G) lg = p.logits + (p.off[it.c] * G + (int64_t)n16 * p.cap[it.c] + it.start);
+
   int t0 = wave * kSlab;
   if (t0 < cnt) {
     BAKLAVA_LOAD_K(t0)
@@ -145,13 +150,20 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
           if (t0 + T * 16 + jg * 4 + i >= cnt) x[T * 4 + i] = kNegInf;
     }
     if (p.track && n16 < G) {
+      // Lane (g, jg) holds 4 consecutive rows of each 16-row tile: one 16-byte store per tile into
+      // head g's run of the cache's stash.  Rows past the item's capacity are not written.
+      typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 #pragma unroll
-      for (int T = 0; T < 2; ++T)
+      for (int T = 0; T < 2; ++T) {
+        const int r = t0 + T * 16 + jg * 4;
+        if (r + 4 <= it.count) {
+          *reinterpret_cast<f32x4_a4*>(lg + r) = f32x4_a4{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = t0 + T * 16 + jg * 4 + i;
-          if (r < cnt) p.logits[(row0 + r) * G + n16] = x[T * 4 + i];
+          for (int i = 0; i < 4; ++i)
+            if (r + i < it.count) lg[r + i] = x[T * 4 + i];
         }
+      }
     }
     float mx = x[0];
 #pragma unroll

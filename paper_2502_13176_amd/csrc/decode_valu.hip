@@ -122,7 +122,8 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
       if (p.track && live) {
 #pragma unroll
         for (int g = 0; g < GT; ++g)
-          if (sub == g && g < G) p.logits[(row0 + r) * G + g] = s[u][g];
+          if (sub == g && g < G)
+            p.logits[p.off[it.c] * G + (int64_t)g * p.cap[it.c] + it.start + r] = s[u][g];
       }
     }
 #pragma unroll
@@ -245,12 +246,14 @@ __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
   const int n = p.len[it.c];
   const int cnt = min(it.start + it.count, n) - it.start;
   const int64_t row0 = p.off[it.c] + it.start;
+  const int64_t cap = p.cap[it.c];
+  const float* lg = p.logits + (p.off[it.c] * G + it.start);
   for (int r = threadIdx.x; r < cnt; r += 256) {
     float w = 0.f;
     for (int g = 0; g < G; ++g) {
       const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
       const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
-      w += fast_exp2(p.logits[(row0 + r) * G + g] - M) * inv;
+      w += fast_exp2(lg[g * cap + r] - M) * inv;
     }
     p.score[row0 + r] += w;
   }

@@ -151,3 +151,28 @@ def test_infeasible_budget_is_refused_at_creation():
     with pytest.raises(B.BaklavaError) as e:
         H.make_arena(w, [19])
     assert e.value.status == B.EINFEASIBLE
+
+
+@pytest.mark.parametrize("slack", [1, 64, 700])
+def test_long_caches_move_in_several_segments(slack):
+    """Budgets around and above the move's segment size (4096 rows): rows whose source lies in the
+    next segment travel through the halo copy."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama32"], name="segs", L=1, Hq=8, Hkv=4, batch=2, seed=25, sink=4,
+                     recent=16, slack=slack)
+    rng = np.random.Generator(np.random.PCG64(w.seed + slack))
+    budgets = [4095, 4096, 4097, 13000]
+    arena = H.make_arena(w, budgets)
+    lens = [b + slack for b in budgets] + [b + max(1, slack // 2) for b in budgets]
+    st = H.fill_from_host(arena, w, lens, rng, scores="uniform")
+    after = run_compact_and_check(arena, w, st)
+    # evictions concentrated at the very front: every later row shifts by the full amount
+    st2 = H.fill_from_host(arena, w, lens, rng, scores="uniform")
+    for c in range(arena.n_caches):
+        s = np.ones(lens[c], dtype=np.float32)
+        s[4:4 + 2 * slack] = 0.0
+        o = int(arena.off_host[c])
+        arena.score[o:o + lens[c]].copy_(torch.from_numpy(s).to(arena.device))
+        st2.score[c] = s
+    run_compact_and_check(arena, w, st2)
+    arena.close()

@@ -97,9 +97,11 @@ def test_workspace_bytes_is_a_pure_host_query():
     d = B.Desc()
     d.L, d.Hq, d.Hkv, d.D, d.batch, d.dtype = w.L, w.Hq, w.Hkv, w.D, w.batch, B.BF16
     d.sink, d.recent = w.sink, w.recent
-    n0 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32)))
+    i32p = C.POINTER(C.c_int32)
+    bud = np.ascontiguousarray(b, dtype=np.int32)
+    n0 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
     d.track_scores = 1
-    n1 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32)))
+    n1 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
     assert n0 > 0 and n1 == n0 + ((total * w.G * 4 + 255) // 256) * 256
     d.D = 96
-    assert B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(C.POINTER(C.c_int32))) == 0
+    assert B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p)) == 0

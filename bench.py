@@ -34,6 +34,7 @@ def parse_args():
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-track", action="store_true", help="do not accumulate attention scores (long workload)")
     ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the extra region in the other launch mode (keeps profiler traces to one mode)")
@@ -133,7 +134,7 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
     budgets = synth.budgets_for(w, B.alloc_proportional)
-    track = w.scores == "kernel"
+    track = w.scores == "kernel" and not args.no_track
     arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack, w.sink, w.recent,
                     B.POLICY_SCORE, track)
     gen = synth.fill_arena_on_device(arena, w)

@@ -39,7 +39,7 @@ struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
   size_t items[2], cib[2], iorder[2], multi[2];
   size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer;
-  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, total;
+  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, stash_off, total;
   int64_t n_segs, halo_rows;
   int64_t max_items;
 };
@@ -94,7 +94,10 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
   w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
   w.final_ml = o;     o = align256(o + (size_t)n_caches * G * 2 * 4);
-  w.logits = o;       o = align256(o + (d->track_scores ? (size_t)total_tokens * G * 4 : 0));
+  int64_t stash_floats = 0;
+  for (int64_t c = 0; c < n_caches; ++c) stash_floats += (int64_t)G * (((int64_t)cap[c] + 31) / 32 * 32);
+  w.logits = o;       o = align256(o + (d->track_scores ? (size_t)stash_floats * 4 : 0));
+  w.stash_off = o;    o = align256(o + (size_t)n_caches * 8);
   w.kept = o;         o = align256(o + (size_t)total_tokens * 4);
   w.info = o;         o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
   w.order_all = o;    o = align256(o + (size_t)n_caches * 4);
@@ -213,6 +216,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
   p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
   p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
+  p.stash_off = reinterpret_cast<const int64_t*>(ctx->ws + ctx->plan.stash_off);
   p.cap = ctx->d.cap;
   p.score = ctx->d.score;
   p.pos = ctx->d.pos;
@@ -322,6 +326,19 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.order_layer, ctx->order_layer.data(), n_caches * 4, hipMemcpyHostToDevice))) {
     delete ctx;
     return BAKLAVA_EHIP;
+  }
+  // Where each cache's logit stash starts (floats).
+  {
+    std::vector<int64_t> so(n_caches);
+    int64_t acc = 0;
+    for (int64_t c = 0; c < n_caches; ++c) {
+      so[c] = acc;
+      acc += (int64_t)ctx->G * (((int64_t)ctx->cap[c] + 31) / 32 * 32);
+    }
+    if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.stash_off, so.data(), n_caches * 8, hipMemcpyHostToDevice))) {
+      delete ctx;
+      return BAKLAVA_EHIP;
+    }
   }
   // Segment table of the eviction move (depends on budgets and capacities only).
   {

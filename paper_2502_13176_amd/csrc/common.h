@@ -37,7 +37,11 @@ struct DecodeParams {
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
   float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
   float* logits;                   // scaled logits in log2 units (track_scores): cache c owns
-                                   // [G * off_c, G * (off_c + cap_c)), query head g at + g * cap_c
+                                   // ceil(cap_c / 32) blocks of [G][32] floats starting at float
+                                   // offset stash_off[c]; row j of head g sits at
+                                   // (j / 32) * 32 G + 32 g + j % 32, so a 32-row slab is one
+                                   // contiguous, 128-byte aligned run of G lines
+  const int64_t* stash_off;
   const int32_t* cap;
   float* score;
   int32_t* pos;

@@ -49,34 +49,27 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_
 #endif
 __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
+  __shared__ __attribute__((aligned(16))) float lds_logit[kWaves][16 * kSlab];  // [head][row] per wavefront
 
   const Item it = p.items[p.order[blockIdx.x]];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, jg = lane >> 4;
   const int G = p.G;
+  // Table entries are read before the fused append stores anything, so that they stay scalar loads.
   const int n_old = p.len[it.c];
+  const int64_t off_c = p.off[it.c];
+  const int64_t stash0 = p.track ? p.stash_off[it.c] : 0;
   const int n = n_old + p.fused_append;
-  if (p.fused_append) append_new_row(p, it, n_old);
+  if (p.fused_append) append_new_row(p, it, n_old, off_c);
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
-  const int64_t row0 = p.off[it.c] + it.start;
+  const int64_t row0 = off_c + it.start;
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.k) + row0 * (kD * 2);
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(p.v) + row0 * (kD * 2);
   unsigned char* myl = lds + wave * (kSlab * kVStride);
 
   const int c_rel = it.c - p.cache_begin;
   const int64_t qrow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
-
-  // B operand of the first product: lane (g, j), chunk c holds Q[g][32c + 8j .. +8).
-  bf16x8_t qb[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    u32x4_t raw = {0u, 0u, 0u, 0u};
-    if (n16 < G)
-      raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(p.q) +
-                                              (qrow0 + n16) * (kD * 2) + c * 64 + jg * 16);
-    qb[c] = as_bf16x8(raw);
-  }
 
   floatx4_t o[8];
 #pragma unroll
@@ -105,16 +98,34 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
     vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + off);                                          \
   }
 
-  // Head n16's run of this cache's logit stash, at the item's first row (loaded once, before the
-  // loop: a load inside the loop would make the in-order wait counter stall on the prefetches).
+  // Logit stash (score tracking): a slab's logits form one contiguous block [G][32]; lane l < 8G
+  // stores 16 bytes of it, so every store instruction writes G whole, adjacent 128-byte lines.
+  // The pointer is formed once, before the loop: a load inside the loop would make the in-order
+  // wait counter stall on the prefetches.
   float* lg = nullptr;
-  if (p.track && n16 < G) lg = p.logits + (p.off[it.c] * G + (int64_t)n16 * p.cap[it.c] + it.start);
+  if (p.track && lane < 8 * G) lg = p.logits + (stash0 + (int64_t)it.start * G + lane * 4);
 
+  // Order of the first loads: K of the first slab, then the query, then V.  The loop's first wait
+  // (for K and, on the first pass, the query) then leaves the V loads in flight, and the stream
+  // starts one memory round trip earlier than with the query fetched first.
   int t0 = wave * kSlab;
   if (t0 < cnt) {
     BAKLAVA_LOAD_K(t0)
+  }
+  // B operand of the first product: lane (g, j), chunk c holds Q[g][32c + 8j .. +8).
+  bf16x8_t qb[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    u32x4_t raw = {0u, 0u, 0u, 0u};
+    if (n16 < G)
+      raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(p.q) +
+                                              (qrow0 + n16) * (kD * 2) + c * 64 + jg * 16);
+    qb[c] = as_bf16x8(raw);
+  }
+  if (t0 < cnt) {
     BAKLAVA_LOAD_V(t0)
   }
+
   for (; t0 < cnt; t0 += kWaves * kSlab) {
     const int tn = t0 + kWaves * kSlab;
 
@@ -149,21 +160,26 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
         for (int i = 0; i < 4; ++i)
           if (t0 + T * 16 + jg * 4 + i >= cnt) x[T * 4 + i] = kNegInf;
     }
-    if (p.track && n16 < G) {
-      // Lane (g, jg) holds 4 consecutive rows of each 16-row tile: one 16-byte store per tile into
-      // head g's run of the cache's stash.  Rows past the item's capacity are not written.
-      typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+    if (p.track) {
+      // Through LDS from the accumulator layout (lane (g, jg): rows 4jg..4jg+3 of each tile) to
+      // one line per head.  Rows past the live length carry -inf and are never read back.
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      float* tl = lds_logit[wave];
+      if (n16 < G) {
 #pragma unroll
-      for (int T = 0; T < 2; ++T) {
-        const int r = t0 + T * 16 + jg * 4;
-        if (r + 4 <= it.count) {
-          *reinterpret_cast<f32x4_a4*>(lg + r) = f32x4_a4{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (r + i < it.count) lg[r + i] = x[T * 4 + i];
-        }
+        for (int T = 0; T < 2; ++T)
+          *reinterpret_cast<f32x4_t*>(tl + n16 * kSlab + T * 16 + jg * 4) =
+              f32x4_t{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#if defined(BAKLAVA_STASH_VARIANT) && BAKLAVA_STASH_VARIANT == 1
+      if (lg && ((t0 >> 7) & 1) == 0)   // timing experiment: every other slab only
+#else
+      if (lg)
+#endif
+        *reinterpret_cast<f32x4_t*>(lg + t0 * G) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4);
     }
     float mx = x[0];
 #pragma unroll

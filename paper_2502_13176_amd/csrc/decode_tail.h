@@ -15,11 +15,12 @@ __device__ __forceinline__ float tail_exp2(float x) { return __builtin_amdgcn_ex
 // [K'; K_t], [V'; V_t] of Eq. 7 inside the attention kernel: the work item whose row range holds
 // slot `n_old` copies the new row there before it starts streaming.  The barrier makes the row
 // visible to every wavefront of this workgroup; no other workgroup reads that slot.
-__device__ __forceinline__ void append_new_row(const DecodeParams& p, const Item& it, int n_old) {
+__device__ __forceinline__ void append_new_row(const DecodeParams& p, const Item& it, int n_old,
+                                               int64_t off_c) {
   if (!(n_old >= it.start && n_old < it.start + it.count)) return;  // uniform over the workgroup
   const int tid = threadIdx.x;
   const int pieces = p.row_bytes / 16;
-  const int64_t row = p.off[it.c] + n_old;
+  const int64_t row = off_c + n_old;
   if (tid < 2 * pieces) {
     const int plane = tid / pieces, piece = tid % pieces;
     const char* src = reinterpret_cast<const char*>(plane ? p.v_new : p.k_new) +

@@ -62,11 +62,12 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
   const int sub = lane % LPR, rg = lane / LPR;
   const int G = p.G;
   const int n_old = p.len[it.c];
+  const int64_t off_c = p.off[it.c];
   const int n = n_old + p.fused_append;
-  if (p.fused_append) append_new_row(p, it, n_old);
+  if (p.fused_append) append_new_row(p, it, n_old, off_c);
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
-  const int64_t row0 = p.off[it.c] + it.start;
+  const int64_t row0 = off_c + it.start;
   const T* Kb = reinterpret_cast<const T*>(p.k) + row0 * D + sub * EPL;
   const T* Vb = reinterpret_cast<const T*>(p.v) + row0 * D + sub * EPL;
 
@@ -123,7 +124,8 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
 #pragma unroll
         for (int g = 0; g < GT; ++g)
           if (sub == g && g < G)
-            p.logits[p.off[it.c] * G + (int64_t)g * p.cap[it.c] + it.start + r] = s[u][g];
+            p.logits[p.stash_off[it.c] + (int64_t)((it.start + r) >> 5) * (32 * G) + 32 * g + ((it.start + r) & 31)] =
+                s[u][g];
       }
     }
 #pragma unroll
@@ -246,14 +248,14 @@ __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
   const int n = p.len[it.c];
   const int cnt = min(it.start + it.count, n) - it.start;
   const int64_t row0 = p.off[it.c] + it.start;
-  const int64_t cap = p.cap[it.c];
-  const float* lg = p.logits + (p.off[it.c] * G + it.start);
+  const float* lg = p.logits + p.stash_off[it.c];
   for (int r = threadIdx.x; r < cnt; r += 256) {
     float w = 0.f;
     for (int g = 0; g < G; ++g) {
       const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
       const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
-      w += fast_exp2(lg[g * cap + r] - M) * inv;
+      const int j = it.start + r;
+      w += fast_exp2(lg[(int64_t)(j >> 5) * (32 * G) + 32 * g + (j & 31)] - M) * inv;
     }
     p.score[row0 + r] += w;
   }

@@ -105,9 +105,9 @@ def stream_probe(torch, B, device, nbytes=1 << 32, reps=5):
     return out
 
 
-def read_traffic():
+def read_traffic(workload, mode):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary (if any)."""
-    path = os.path.join(ROOT, "profiles", "decode_partial_mfma_llama32_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"decode_partial_mfma_{workload}_{mode}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -229,7 +229,7 @@ def main():
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "roofline": {
             "bound": "hbm", "kernel": "decode_partial", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(),
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(w.name, args.mode),
             "launches": int(launches), "avg_launch_us": round(avg_launch_s * 1e6, 2),
             "algorithmic_bytes_per_launch": int(avg_launch_bytes),
         },

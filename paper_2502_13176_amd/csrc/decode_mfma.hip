@@ -174,11 +174,7 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#if defined(BAKLAVA_STASH_VARIANT) && BAKLAVA_STASH_VARIANT == 1
-      if (lg && ((t0 >> 7) & 1) == 0)   // timing experiment: every other slab only
-#else
       if (lg)
-#endif
         *reinterpret_cast<f32x4_t*>(lg + t0 * G) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4);
     }
     float mx = x[0];

@@ -174,8 +174,9 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      if (lg)
-        *reinterpret_cast<f32x4_t*>(lg + t0 * G) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4);
+      if (lg) *reinterpret_cast<f32x4_t*>(lg + t0 * G) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4);
+      if (lg && lane + 64 < 8 * G)  // more than 8 query heads: the block has a second kilobyte
+        *reinterpret_cast<f32x4_t*>(lg + t0 * G + 256) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4 + 256);
     }
     float mx = x[0];
 #pragma unroll

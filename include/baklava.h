@@ -92,6 +92,27 @@ int baklava_alloc_threshold(const double* importance, int32_t m, const int32_t* 
 int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int32_t batch, int32_t slack,
                    int64_t* off_out, int32_t* cap_out, int64_t* total_tokens_out);
 
+/*
+ * Split-K schedule for decode attention over ragged caches: every cache is cut over its whole
+ * capacity into runs of `chunk` rows (the kernels clamp a run to the live length, so the table
+ * depends on capacities only).  The table is written in launch order, long caches first:
+ * inside each layer when whole_model == 0 (a layer range is then a contiguous slice), over all
+ * layers when whole_model == 1.  Partial slots are numbered cache by cache, so cache c owns the
+ * `nsplit` consecutive slots that start at the slot of its first run.
+ * off_host HOST int64 [L*caches_per_layer], cap_host HOST int32 [same]; chunk a multiple of 64,
+ * >= 256; items_out HOST [max_items] or NULL (count only); n_items_out HOST scalar.
+ * Errors: EINVAL, ECAPACITY (more than max_items work items; n_items_out still receives the count).
+ */
+typedef struct {
+  int32_t cache, start, count, slot;  /* rows [start, start+count) of `cache`; partial slot      */
+  int32_t nsplit;                     /* work items of this cache                                */
+  int32_t reserved;
+  int64_t row0;                       /* arena row of `start`: off[cache] + start                */
+} baklava_work_item;
+int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
+                          int32_t caches_per_layer, int32_t chunk, int32_t whole_model,
+                          int64_t max_items, baklava_work_item* items_out, int64_t* n_items_out);
+
 /* ------------------------------------------------------------------------------------------
  * Device.
  * ------------------------------------------------------------------------------------------ */

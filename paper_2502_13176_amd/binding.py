@@ -25,7 +25,8 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
     "baklava_strerror", "baklava_last_hip_error", "baklava_alloc_proportional",
-    "baklava_alloc_threshold", "baklava_layout", "baklava_workspace_bytes", "baklava_create",
+    "baklava_alloc_threshold", "baklava_layout", "baklava_plan_schedule", "baklava_workspace_bytes",
+    "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
     "baklava_stream_probe",
@@ -49,6 +50,11 @@ class Desc(C.Structure):
     ]
 
 
+class WorkItem(C.Structure):
+    _fields_ = [("cache", C.c_int32), ("start", C.c_int32), ("count", C.c_int32), ("slot", C.c_int32),
+                ("nsplit", C.c_int32), ("reserved", C.c_int32), ("row0", C.c_int64)]
+
+
 _lib = None
 
 
@@ -68,6 +74,8 @@ def lib() -> C.CDLL:
     L.baklava_alloc_proportional.argtypes = [f64p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, i32p]
     L.baklava_alloc_threshold.argtypes = [f64p, C.c_int32, i32p, C.c_double, C.c_double, i32p]
     L.baklava_layout.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i64p, i32p, i64p]
+    L.baklava_plan_schedule.argtypes = [i64p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                        C.POINTER(WorkItem), i64p]
     L.baklava_workspace_bytes.restype = C.c_size_t
     L.baklava_workspace_bytes.argtypes = [C.POINTER(Desc), i32p, i32p]
     L.baklava_create.argtypes = [C.POINTER(Desc), i64p, i32p, i32p, i32p, C.POINTER(C.c_void_p)]
@@ -137,6 +145,21 @@ def layout(budget: Sequence[int], L: int, Hkv: int, batch: int, slack: int):
     _check(lib().baklava_layout(_p(b, C.c_int32), L, Hkv, batch, slack, _p(off, C.c_int64),
                                 _p(cap, C.c_int32), C.byref(total)), "baklava_layout")
     return off, cap, int(total.value)
+
+
+def plan_schedule(off, cap, L: int, caches_per_layer: int, chunk: int, whole_model: bool, max_items=None):
+    """baklava_plan_schedule: list of (cache, start, count, slot, nsplit, row0) in launch order."""
+    off = np.ascontiguousarray(off, dtype=np.int64)
+    cap = _i32(cap)
+    n = C.c_int64(0)
+    st = lib().baklava_plan_schedule(_p(off, C.c_int64), _p(cap, C.c_int32), L, caches_per_layer, chunk,
+                                     int(bool(whole_model)), 0, None, C.byref(n))
+    _check(st, "baklava_plan_schedule")
+    cap_items = int(n.value) if max_items is None else int(max_items)
+    items = (WorkItem * max(1, cap_items))()
+    _check(lib().baklava_plan_schedule(_p(off, C.c_int64), _p(cap, C.c_int32), L, caches_per_layer, chunk,
+                                       int(bool(whole_model)), cap_items, items, C.byref(n)), "baklava_plan_schedule")
+    return [(it.cache, it.start, it.count, it.slot, it.nsplit, it.row0) for it in items[: int(n.value)]]
 
 
 # ---------------------------------------------------------------------------

@@ -37,7 +37,7 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 
 struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
-  size_t items[2], cib[2], iorder[2], multi[2];
+  size_t items[2], cib[2], multi[2];
   size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer;
   size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, stash_off, total;
   int64_t n_segs, halo_rows;
@@ -88,7 +88,6 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   for (int k = 0; k < 2; ++k) {
     w.items[k] = o;   o = align256(o + (size_t)w.max_items * sizeof(Item));
     w.cib[k] = o;     o = align256(o + (size_t)(n_caches + 1) * 4);
-    w.iorder[k] = o;  o = align256(o + (size_t)w.max_items * 4);
     w.multi[k] = o;   o = align256(o + (size_t)n_caches * 4);
   }
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
@@ -139,46 +138,35 @@ struct baklava_ctx {
 
 namespace {
 
-// Cuts every cache into runs of `chunk` rows over its whole capacity.  The table depends on the
-// capacities only, so it is uploaded once; the kernels clamp each run to the live length.
-// Schedule 0 serves launches over a layer sub-range: items are ordered layer by layer, inside a
-// layer long caches first, so a layer range is a contiguous slice.  Schedule 1 serves launches
-// over the whole model: long caches first over all layers.
+// Builds one of the two split-K schedules with the host planner and uploads it.  Schedule 0
+// serves launches over a layer sub-range (launch order inside each layer, so a layer range is a
+// contiguous slice), schedule 1 launches over the whole model.  The table depends on capacities
+// only, so it is uploaded once; the kernels clamp each run to the live length.
 int build_schedule(baklava_ctx* ctx, int which, int chunk) {
-  std::vector<Item> items;
-  std::vector<int32_t> cib(ctx->n_caches + 1);
-  items.reserve((size_t)count_items(ctx->cap.data(), ctx->n_caches, chunk));
-  for (int64_t c = 0; c < ctx->n_caches; ++c) {
-    cib[c] = (int32_t)items.size();
-    const int32_t cap = ctx->cap[c];
-    const int32_t n_runs = std::max(1, (cap + chunk - 1) / chunk);
-    for (int32_t s = 0; s < n_runs; ++s) {
-      Item it;
-      it.c = (int32_t)c;
-      it.start = s * chunk;
-      it.count = std::max(0, std::min(chunk, cap - s * chunk));
-      it.slot = (int32_t)items.size();
-      items.push_back(it);
+  int64_t n_items = 0;
+  std::vector<baklava_work_item> items((size_t)ctx->plan.max_items);
+  const int st = baklava_plan_schedule(ctx->off.data(), ctx->cap.data(), ctx->d.L, ctx->cpl, chunk, which,
+                                       ctx->plan.max_items, items.data(), &n_items);
+  if (st != BAKLAVA_OK) return st;
+  static_assert(sizeof(baklava_work_item) == sizeof(Item), "work item layouts must match");
+  // cache -> first partial slot, and the caches that need the combine kernel (in launch order)
+  std::vector<int32_t> cib(ctx->n_caches + 1, 0), multi, multi_begin(ctx->d.L + 1, 0);
+  for (int64_t i = 0; i < n_items; ++i) {
+    const baklava_work_item& it = items[i];
+    if (it.start == 0) {
+      cib[it.cache] = it.slot;
+      if (it.nsplit > 1) {
+        multi.push_back(it.cache);
+        multi_begin[it.cache / ctx->cpl + 1] += 1;
+      }
     }
   }
-  cib[ctx->n_caches] = (int32_t)items.size();
-  if ((int64_t)items.size() > ctx->plan.max_items) return BAKLAVA_ECAPACITY;
-  const std::vector<int32_t>& corder = which == 0 ? ctx->order_layer : ctx->order_all;
-  std::vector<int32_t> iorder, multi, multi_begin(ctx->d.L + 1, 0);
-  iorder.reserve(items.size());
-  for (int32_t c : corder) {
-    for (int32_t i = cib[c]; i < cib[c + 1]; ++i) iorder.push_back(i);
-    if (cib[c + 1] - cib[c] > 1) {  // needs the combine kernel
-      multi.push_back(c);
-      multi_begin[c / ctx->cpl + 1] += 1;
-    }
-  }
+  cib[ctx->n_caches] = (int32_t)n_items;
   for (int32_t l = 0; l < ctx->d.L; ++l) multi_begin[l + 1] += multi_begin[l];
   if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
-  const size_t ni = items.size();
-  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items[which], items.data(), ni * sizeof(Item), hipMemcpyHostToDevice)) ||
+  if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items[which], items.data(), (size_t)n_items * sizeof(Item),
+                        hipMemcpyHostToDevice)) ||
       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib[which], cib.data(), cib.size() * 4, hipMemcpyHostToDevice)) ||
-      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.iorder[which], iorder.data(), ni * 4, hipMemcpyHostToDevice)) ||
       (!multi.empty() &&
        !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi[which], multi.data(), multi.size() * 4, hipMemcpyHostToDevice))))
     return BAKLAVA_EHIP;
@@ -208,9 +196,9 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   DecodeParams p;
   p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
   p.off = ctx->d.off; p.len = ctx->d.len;
-  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]);
-  // Items are numbered cache by cache, so a layer range is the slice [i0, i1) of the per-layer order.
-  p.order = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.iorder[which]) + i0;
+  // Slots are numbered cache by cache and the launch order only permutes caches inside a layer
+  // (schedule 0), so the launch-ordered table of a layer range is the slice [i0, i1).
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]) + i0;
   p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib[which]);
   p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);

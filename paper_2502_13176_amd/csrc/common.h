@@ -9,10 +9,14 @@ namespace baklava {
 
 constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move
 
-// One split-K work item: rows [start, start + count) of cache c; its partial result goes to
-// partial slot `slot`.  Rows at or beyond the cache's live length are skipped by the kernel.
+// One split-K work item (same layout as baklava_work_item of the public header): rows
+// [start, start + count) of cache c; its partial result goes to partial slot `slot`.  Rows at or
+// beyond the cache's live length are skipped by the kernel.
 struct Item {
   int32_t c, start, count, slot;
+  int32_t nsplit;  // work items of this cache
+  int32_t pad;
+  int64_t row0;    // arena row of `start`: off[c] + start
 };
 
 // Result of the selection pass for one cache.
@@ -30,8 +34,7 @@ struct DecodeParams {
   float* out;
   const int64_t* off;
   int32_t* len;
-  const Item* items;               // whole table, indexed by item id
-  const int32_t* order;            // launch order of the launched range: blockIdx.x -> item id
+  const Item* items;               // work items of the launched range, in launch order
   const int32_t* cache_item_begin; // [n_caches + 1], absolute item index
   float* part_o;                   // [n_items, G, D] un-normalised partial outputs
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)

@@ -51,13 +51,13 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
   __shared__ __attribute__((aligned(16))) float lds_logit[kWaves][16 * kSlab];  // [head][row] per wavefront
 
-  const Item it = p.items[p.order[blockIdx.x]];
+  const Item it = p.items[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, jg = lane >> 4;
   const int G = p.G;
   // Table entries are read before the fused append stores anything, so that they stay scalar loads.
   const int n_old = p.len[it.c];
-  const int64_t off_c = p.off[it.c];
+  const int64_t off_c = it.row0 - it.start;
   const int64_t stash0 = p.track ? p.stash_off[it.c] : 0;
   const int n = n_old + p.fused_append;
   if (p.fused_append) append_new_row(p, it, n_old, off_c);

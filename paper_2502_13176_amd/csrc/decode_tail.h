@@ -44,7 +44,7 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
                                             const float* sm_o, const float* sm_m, const float* sm_l) {
   const int tid = threadIdx.x;
   const int c = it.c;
-  const bool single = (p.cache_item_begin[c + 1] - p.cache_item_begin[c]) == 1;
+  const bool single = it.nsplit == 1;
   const int c_rel = c - p.cache_begin;
   const int64_t orow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
 

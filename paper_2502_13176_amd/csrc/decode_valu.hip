@@ -57,12 +57,12 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
   constexpr int TILE = RPW * U;
   constexpr int NW = 4;
 
-  const Item it = p.items[p.order[blockIdx.x]];
+  const Item it = p.items[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rg = lane / LPR;
   const int G = p.G;
   const int n_old = p.len[it.c];
-  const int64_t off_c = p.off[it.c];
+  const int64_t off_c = it.row0 - it.start;
   const int n = n_old + p.fused_append;
   if (p.fused_append) append_new_row(p, it, n_old, off_c);
   int cnt = min(it.start + it.count, n) - it.start;
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
 // score_j += sum_g 2^(s_gj - M_g) / L_g  (cumulative attention per cached token, summed over the
 // query heads that share the cache).
 __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
-  const Item it = p.items[p.order[blockIdx.x]];
+  const Item it = p.items[blockIdx.x];
   const int G = p.G;
   const int n = p.len[it.c];
   const int cnt = min(it.start + it.count, n) - it.start;

@@ -147,3 +147,50 @@ extern "C" int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int
   *total_tokens_out = total;
   return BAKLAVA_OK;
 }
+
+// Split-K schedule: runs of `chunk` rows over each cache's capacity, in launch order.
+extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
+                                     int32_t caches_per_layer, int32_t chunk, int32_t whole_model,
+                                     int64_t max_items, baklava_work_item* items_out, int64_t* n_items_out) {
+  if (!off_host || !cap_host || !n_items_out || L <= 0 || caches_per_layer <= 0) return BAKLAVA_EINVAL;
+  if (chunk < 256 || chunk % 64 || chunk > (1 << 22) || max_items < 0) return BAKLAVA_EINVAL;
+  if (whole_model != 0 && whole_model != 1) return BAKLAVA_EINVAL;
+  const int64_t n_caches = (int64_t)L * caches_per_layer;
+  std::vector<int64_t> first_slot(n_caches + 1, 0);
+  for (int64_t c = 0; c < n_caches; ++c) {
+    if (cap_host[c] < 0 || off_host[c] < 0) return BAKLAVA_EINVAL;
+    first_slot[c + 1] = first_slot[c] + std::max<int64_t>(1, ((int64_t)cap_host[c] + chunk - 1) / chunk);
+  }
+  const int64_t n_items = first_slot[n_caches];
+  *n_items_out = n_items;
+  if (n_items > INT32_MAX) return BAKLAVA_EINVAL;
+  if (!items_out) return BAKLAVA_OK;
+  if (n_items > max_items) return BAKLAVA_ECAPACITY;
+  // cache order: longest capacity first (stable), inside each layer or over the whole model
+  std::vector<int32_t> order(n_caches);
+  std::iota(order.begin(), order.end(), 0);
+  auto longer = [&](int32_t a, int32_t b) { return cap_host[a] > cap_host[b]; };
+  if (whole_model) {
+    std::stable_sort(order.begin(), order.end(), longer);
+  } else {
+    for (int32_t l = 0; l < L; ++l)
+      std::stable_sort(order.begin() + (int64_t)l * caches_per_layer,
+                       order.begin() + (int64_t)(l + 1) * caches_per_layer, longer);
+  }
+  int64_t k = 0;
+  for (int32_t c : order) {
+    const int32_t cap = cap_host[c];
+    const int32_t nsplit = (int32_t)(first_slot[c + 1] - first_slot[c]);
+    for (int32_t s = 0; s < nsplit; ++s) {
+      baklava_work_item& it = items_out[k++];
+      it.cache = c;
+      it.start = s * chunk;
+      it.count = std::max(0, std::min(chunk, cap - s * chunk));
+      it.slot = (int32_t)(first_slot[c] + s);
+      it.nsplit = nsplit;
+      it.reserved = 0;
+      it.row0 = off_host[c] + it.start;
+    }
+  }
+  return BAKLAVA_OK;
+}

@@ -106,3 +106,56 @@ def test_workspace_bytes_is_a_pure_host_query():
     assert n0 > 0 and n1 == n0 + ((stash + 255) // 256) * 256
     d.D = 96
     assert B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p)) == 0
+
+
+@pytest.mark.parametrize("name,chunk", [("llama32", 512), ("llama32", 2048), ("qwen", 768), ("long", 4096), ("tiny", 256)])
+@pytest.mark.parametrize("whole", [False, True])
+def test_split_k_schedule_covers_every_row_once(name, chunk, whole):
+    w = synth.WORKLOADS[name]
+    b = synth.budgets_for(w, B.alloc_proportional)
+    off, cap, total = B.layout(b, w.L, w.Hkv, w.batch, w.slack)
+    cpl = w.batch * w.Hkv
+    items = B.plan_schedule(off, cap, w.L, cpl, chunk, whole)
+    n_caches = w.L * cpl
+    seen_rows = np.zeros(n_caches, dtype=np.int64)
+    slots = set()
+    first_slot = {}
+    for (c, start, count, slot, nsplit, row0) in items:
+        assert 0 <= count <= chunk and start % chunk == 0 and start + count <= cap[c]
+        assert row0 == off[c] + start
+        assert nsplit == max(1, -(-int(cap[c]) // chunk))
+        assert slot not in slots
+        slots.add(slot)
+        seen_rows[c] += count
+        first_slot.setdefault(c, slot - start // chunk)
+        assert slot == first_slot[c] + start // chunk          # a cache's slots are consecutive
+    assert slots == set(range(len(items)))                      # slots are a permutation of 0..n-1
+    assert np.array_equal(seen_rows, cap.astype(np.int64))     # every row of every cache exactly once
+    # slots are numbered cache by cache
+    assert [first_slot[c] for c in range(n_caches)] == sorted(first_slot[c] for c in range(n_caches))
+    caches_in_order = [it[0] for it in items if it[1] == 0]
+    if whole:
+        caps = [int(cap[c]) for c in caches_in_order]
+        assert caps == sorted(caps, reverse=True)               # long caches first over the whole model
+    else:
+        for l in range(w.L):                                    # a layer is a contiguous slice, long first
+            sl = caches_in_order[l * cpl:(l + 1) * cpl]
+            assert sorted(sl) == list(range(l * cpl, (l + 1) * cpl))
+            caps = [int(cap[c]) for c in sl]
+            assert caps == sorted(caps, reverse=True)
+            lo = min(it[3] for it in items if it[0] in sl)
+            n_l = sum(1 for it in items if it[0] in set(sl))
+            pos = [i for i, it in enumerate(items) if it[0] in set(sl)]
+            assert pos == list(range(lo, lo + n_l))             # launch positions == slot range of the layer
+
+
+def test_split_k_schedule_errors():
+    off, cap, _ = B.layout([300, 5000], 1, 2, 1, 0)
+    for bad_chunk in (0, 100, 255, 300, (1 << 22) + 64):
+        with pytest.raises(B.BaklavaError) as e:
+            B.plan_schedule(off, cap, 1, 2, bad_chunk, False)
+        assert e.value.status == B.EINVAL
+    assert len(B.plan_schedule(off, cap, 1, 2, 256, False)) == 2 + 20
+    with pytest.raises(B.BaklavaError) as e:
+        B.plan_schedule(off, cap, 1, 2, 256, False, max_items=5)
+    assert e.value.status == B.ECAPACITY

@@ -99,6 +99,11 @@ int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int32_t batch,
  * inside each layer when whole_model == 0 (a layer range is then a contiguous slice), over all
  * layers when whole_model == 1.  Partial slots are numbered cache by cache, so cache c owns the
  * `nsplit` consecutive slots that start at the slot of its first run.
+ * With target_items > 0 a launch unit (each layer when whole_model == 0, the whole model
+ * otherwise) that would have more than max(target_items, caches in the unit) work items gets
+ * longer runs: the smallest multiple of 64 that brings it to that many items -- e.g. one
+ * workgroup per compute unit, so that a launch is one even wave of workgroups -- after which the
+ * runs inside each cache are made equal (rounded up to 64 rows) without adding an item.
  * off_host HOST int64 [L*caches_per_layer], cap_host HOST int32 [same]; chunk a multiple of 64,
  * >= 256; items_out HOST [max_items] or NULL (count only); n_items_out HOST scalar.
  * Errors: EINVAL, ECAPACITY (more than max_items work items; n_items_out still receives the count).
@@ -110,8 +115,9 @@ typedef struct {
   int64_t row0;                       /* arena row of `start`: off[cache] + start                */
 } baklava_work_item;
 int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
-                          int32_t caches_per_layer, int32_t chunk, int32_t whole_model,
-                          int64_t max_items, baklava_work_item* items_out, int64_t* n_items_out);
+                          int32_t caches_per_layer, int32_t chunk, int32_t target_items,
+                          int32_t whole_model, int64_t max_items, baklava_work_item* items_out,
+                          int64_t* n_items_out);
 
 /* ------------------------------------------------------------------------------------------
  * Device.
@@ -166,7 +172,10 @@ enum {
                                    (multiple of 64, >= 256)                                          */
   BAKLAVA_OPT_KERNEL = 2,       /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
   BAKLAVA_OPT_TIME_KERNEL = 3,  /* 1: bracket every attention partial-kernel launch with HIP events  */
-  BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4 /* rows per work item for launches over all layers at once      */
+  BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* rows per work item for launches over all layers at once     */
+  BAKLAVA_OPT_TARGET_ITEMS = 5  /* > 0: launches over part of the layers lengthen their runs, layer by
+                                   layer, until a layer has at most this many work items; 0: off.
+                                   Default: the device's number of compute units                    */
 };
 int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
 

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("BAKLAVA_LIB") or os.path.join(HERE, "libbaklava.so")
 OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
 BF16, F32 = 0, 1
 POLICY_SCORE, POLICY_STREAMING = 0, 1
-OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL, OPT_CHUNK_TOKENS_WHOLE = 1, 2, 3, 4
+OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL, OPT_CHUNK_TOKENS_WHOLE, OPT_TARGET_ITEMS = 1, 2, 3, 4, 5
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [
@@ -74,8 +74,8 @@ def lib() -> C.CDLL:
     L.baklava_alloc_proportional.argtypes = [f64p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, i32p]
     L.baklava_alloc_threshold.argtypes = [f64p, C.c_int32, i32p, C.c_double, C.c_double, i32p]
     L.baklava_layout.argtypes = [i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, i64p, i32p, i64p]
-    L.baklava_plan_schedule.argtypes = [i64p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
-                                        C.POINTER(WorkItem), i64p]
+    L.baklava_plan_schedule.argtypes = [i64p, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_int64, C.POINTER(WorkItem), i64p]
     L.baklava_workspace_bytes.restype = C.c_size_t
     L.baklava_workspace_bytes.argtypes = [C.POINTER(Desc), i32p, i32p]
     L.baklava_create.argtypes = [C.POINTER(Desc), i64p, i32p, i32p, i32p, C.POINTER(C.c_void_p)]
@@ -147,18 +147,18 @@ def layout(budget: Sequence[int], L: int, Hkv: int, batch: int, slack: int):
     return off, cap, int(total.value)
 
 
-def plan_schedule(off, cap, L: int, caches_per_layer: int, chunk: int, whole_model: bool, max_items=None):
+def plan_schedule(off, cap, L: int, caches_per_layer: int, chunk: int, whole_model: bool, max_items=None,
+                  target_items: int = 0):
     """baklava_plan_schedule: list of (cache, start, count, slot, nsplit, row0) in launch order."""
     off = np.ascontiguousarray(off, dtype=np.int64)
     cap = _i32(cap)
     n = C.c_int64(0)
-    st = lib().baklava_plan_schedule(_p(off, C.c_int64), _p(cap, C.c_int32), L, caches_per_layer, chunk,
-                                     int(bool(whole_model)), 0, None, C.byref(n))
-    _check(st, "baklava_plan_schedule")
+    args = (_p(off, C.c_int64), _p(cap, C.c_int32), L, caches_per_layer, chunk, int(target_items),
+            int(bool(whole_model)))
+    _check(lib().baklava_plan_schedule(*args, 0, None, C.byref(n)), "baklava_plan_schedule")
     cap_items = int(n.value) if max_items is None else int(max_items)
     items = (WorkItem * max(1, cap_items))()
-    _check(lib().baklava_plan_schedule(_p(off, C.c_int64), _p(cap, C.c_int32), L, caches_per_layer, chunk,
-                                       int(bool(whole_model)), cap_items, items, C.byref(n)), "baklava_plan_schedule")
+    _check(lib().baklava_plan_schedule(*args, cap_items, items, C.byref(n)), "baklava_plan_schedule")
     return [(it.cache, it.start, it.count, it.slot, it.nsplit, it.row0) for it in items[: int(n.value)]]
 
 

@@ -124,8 +124,10 @@ struct baklava_ctx {
   std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
   std::vector<int32_t> seg_begin;               // cache -> first segment of the eviction move
   int32_t kernel_pref;
+  int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
   struct Schedule {
     int32_t chunk = 0;
+    int32_t max_count = 0;             // longest work item, rows
     std::vector<int32_t> cib;          // cache -> first item
     std::vector<int32_t> multi_begin;  // layer -> first entry of the list of multi-item caches
   } sched[2];                          // 0: layer sub-range launches, 1: whole-model launches
@@ -145,14 +147,17 @@ namespace {
 int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   int64_t n_items = 0;
   std::vector<baklava_work_item> items((size_t)ctx->plan.max_items);
-  const int st = baklava_plan_schedule(ctx->off.data(), ctx->cap.data(), ctx->d.L, ctx->cpl, chunk, which,
-                                       ctx->plan.max_items, items.data(), &n_items);
+  const int st = baklava_plan_schedule(ctx->off.data(), ctx->cap.data(), ctx->d.L, ctx->cpl, chunk,
+                                       which == 0 ? ctx->target_items : 0, which, ctx->plan.max_items,
+                                       items.data(), &n_items);
   if (st != BAKLAVA_OK) return st;
   static_assert(sizeof(baklava_work_item) == sizeof(Item), "work item layouts must match");
   // cache -> first partial slot, and the caches that need the combine kernel (in launch order)
   std::vector<int32_t> cib(ctx->n_caches + 1, 0), multi, multi_begin(ctx->d.L + 1, 0);
+  int32_t max_count = 0;
   for (int64_t i = 0; i < n_items; ++i) {
     const baklava_work_item& it = items[i];
+    max_count = std::max(max_count, it.count);
     if (it.start == 0) {
       cib[it.cache] = it.slot;
       if (it.nsplit > 1) {
@@ -173,6 +178,7 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   ctx->sched[which].cib.swap(cib);
   ctx->sched[which].multi_begin.swap(multi_begin);
   ctx->sched[which].chunk = chunk;
+  ctx->sched[which].max_count = max_count;
   return BAKLAVA_OK;
 }
 
@@ -242,7 +248,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
   if (fused)
     for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
-  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, s))) return BAKLAVA_EHIP;
+  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, sc.max_count, s))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;
 }
 
@@ -295,6 +301,16 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
   else ctx->len.assign(n_caches, 0);
   ctx->budget.assign(budget_host, budget_host + m);
   ctx->kernel_pref = 0;
+  // A launch over part of the layers is one wave of workgroups: at most one per compute unit.
+  {
+    int dev = 0, cus = 0;
+    if (!hip_ok(hipGetDevice(&dev)) ||
+        !hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) {
+      delete ctx;
+      return BAKLAVA_EHIP;
+    }
+    ctx->target_items = cus;
+  }
   ctx->time_kernel = false;
   ctx->ev_used = 0;
   ctx->plan = plan_workspace(desc, cap_host, budget_host);
@@ -380,6 +396,11 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       if ((int32_t)value == ctx->sched[which].chunk) return BAKLAVA_OK;
       return build_schedule(ctx, which, (int32_t)value);
     }
+    case BAKLAVA_OPT_TARGET_ITEMS:
+      if (value < 0 || value > (1 << 20)) return BAKLAVA_EINVAL;
+      if ((int32_t)value == ctx->target_items) return BAKLAVA_OK;
+      ctx->target_items = (int32_t)value;
+      return build_schedule(ctx, 0, ctx->sched[0].chunk);
     case BAKLAVA_OPT_KERNEL:
       if (value < 0 || value > 2) return BAKLAVA_EINVAL;
       if (value == 2 && !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_EINVAL;

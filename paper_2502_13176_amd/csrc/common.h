@@ -111,7 +111,8 @@ struct CompactParams {
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s);
-hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s);
+// max_count: the largest row count of a work item in the launched range (or a bound on it)
+hipError_t launch_score_update(const DecodeParams& p, int n_items, int max_count, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
 hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s);

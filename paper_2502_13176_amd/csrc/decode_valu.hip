@@ -241,15 +241,19 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
 }
 
 // score_j += sum_g 2^(s_gj - M_g) / L_g  (cumulative attention per cached token, summed over the
-// query heads that share the cache).
+// query heads that share the cache).  Workgroup (x, y) updates rows [y * kScoreTile, +kScoreTile)
+// of work item x, so that long work items still spread over many workgroups.
+constexpr int kScoreTile = 1024;
 __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
   const Item it = p.items[blockIdx.x];
   const int G = p.G;
   const int n = p.len[it.c];
-  const int cnt = min(it.start + it.count, n) - it.start;
+  const int r0 = blockIdx.y * kScoreTile;
+  const int cnt = min(min(it.start + it.count, n) - it.start, r0 + kScoreTile);
+  if (r0 >= cnt) return;
   const int64_t row0 = p.off[it.c] + it.start;
   const float* lg = p.logits + p.stash_off[it.c];
-  for (int r = threadIdx.x; r < cnt; r += 256) {
+  for (int r = r0 + threadIdx.x; r < cnt; r += 256) {
     float w = 0.f;
     for (int g = 0; g < G; ++g) {
       const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
@@ -319,9 +323,9 @@ hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_score_update(const DecodeParams& p, int n_items, hipStream_t s) {
-  if (n_items <= 0) return hipSuccess;
-  score_update_kernel<<<dim3(n_items), dim3(256), 0, s>>>(p);
+hipError_t launch_score_update(const DecodeParams& p, int n_items, int max_count, hipStream_t s) {
+  if (n_items <= 0 || max_count <= 0) return hipSuccess;
+  score_update_kernel<<<dim3(n_items, (max_count + kScoreTile - 1) / kScoreTile), dim3(256), 0, s>>>(p);
   return hipGetLastError();
 }
 

@@ -148,19 +148,51 @@ extern "C" int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int
   return BAKLAVA_OK;
 }
 
-// Split-K schedule: runs of `chunk` rows over each cache's capacity, in launch order.
+// Split-K schedule: runs of equal length over each cache's capacity, in launch order.
 extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
-                                     int32_t caches_per_layer, int32_t chunk, int32_t whole_model,
-                                     int64_t max_items, baklava_work_item* items_out, int64_t* n_items_out) {
+                                     int32_t caches_per_layer, int32_t chunk, int32_t target_items,
+                                     int32_t whole_model, int64_t max_items, baklava_work_item* items_out,
+                                     int64_t* n_items_out) {
   if (!off_host || !cap_host || !n_items_out || L <= 0 || caches_per_layer <= 0) return BAKLAVA_EINVAL;
-  if (chunk < 256 || chunk % 64 || chunk > (1 << 22) || max_items < 0) return BAKLAVA_EINVAL;
+  if (chunk < 256 || chunk % 64 || chunk > (1 << 22) || max_items < 0 || target_items < 0) return BAKLAVA_EINVAL;
   if (whole_model != 0 && whole_model != 1) return BAKLAVA_EINVAL;
   const int64_t n_caches = (int64_t)L * caches_per_layer;
-  std::vector<int64_t> first_slot(n_caches + 1, 0);
-  for (int64_t c = 0; c < n_caches; ++c) {
+  for (int64_t c = 0; c < n_caches; ++c)
     if (cap_host[c] < 0 || off_host[c] < 0) return BAKLAVA_EINVAL;
-    first_slot[c + 1] = first_slot[c] + std::max<int64_t>(1, ((int64_t)cap_host[c] + chunk - 1) / chunk);
+  auto runs = [&](int64_t c, int64_t run) { return std::max<int64_t>(1, ((int64_t)cap_host[c] + run - 1) / run); };
+  auto round64 = [](int64_t x) { return (x + 63) / 64 * 64; };
+  // run length of every cache: `chunk`, or what the item target of its launch unit (a layer, or
+  // the whole model) asks for
+  const int64_t n_units = whole_model ? 1 : L;
+  const int64_t unit_caches = whole_model ? n_caches : caches_per_layer;
+  std::vector<int64_t> cache_run(n_caches, chunk);
+  if (target_items > 0) {
+    for (int64_t u = 0; u < n_units; ++u) {
+      const int64_t c0 = u * unit_caches, c1 = c0 + unit_caches;
+      auto items_at = [&](int64_t run) {
+        int64_t n = 0;
+        for (int64_t c = c0; c < c1; ++c) n += runs(c, run);
+        return n;
+      };
+      // a unit never has fewer items than caches
+      const int64_t target = std::max<int64_t>(target_items, unit_caches);
+      if (items_at(chunk) <= target) continue;
+      // the shortest run length, in steps of 64 rows, that meets the target (items_at is non-increasing)
+      int64_t lo = chunk / 64, hi = (int64_t(1) << 31) / 64;
+      while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) / 2;
+        if (items_at(mid * 64) > target) lo = mid; else hi = mid;
+      }
+      const int64_t unit_run = hi * 64;
+      // inside a cache the runs are then made equal: no run grows, the count stays
+      for (int64_t c = c0; c < c1; ++c) {
+        const int64_t n = runs(c, unit_run);
+        cache_run[c] = std::max<int64_t>(chunk, round64(((int64_t)cap_host[c] + n - 1) / n));
+      }
+    }
   }
+  std::vector<int64_t> first_slot(n_caches + 1, 0);
+  for (int64_t c = 0; c < n_caches; ++c) first_slot[c + 1] = first_slot[c] + runs(c, cache_run[c]);
   const int64_t n_items = first_slot[n_caches];
   *n_items_out = n_items;
   if (n_items > INT32_MAX) return BAKLAVA_EINVAL;
@@ -180,12 +212,13 @@ extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap
   int64_t k = 0;
   for (int32_t c : order) {
     const int32_t cap = cap_host[c];
+    const int64_t run = cache_run[c];
     const int32_t nsplit = (int32_t)(first_slot[c + 1] - first_slot[c]);
     for (int32_t s = 0; s < nsplit; ++s) {
       baklava_work_item& it = items_out[k++];
       it.cache = c;
-      it.start = s * chunk;
-      it.count = std::max(0, std::min(chunk, cap - s * chunk));
+      it.start = (int32_t)(s * run);
+      it.count = (int32_t)std::max<int64_t>(0, std::min<int64_t>(run, cap - s * run));
       it.slot = (int32_t)(first_slot[c] + s);
       it.nsplit = nsplit;
       it.reserved = 0;

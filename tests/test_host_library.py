@@ -110,25 +110,53 @@ def test_workspace_bytes_is_a_pure_host_query():
 
 @pytest.mark.parametrize("name,chunk", [("llama32", 512), ("llama32", 2048), ("qwen", 768), ("long", 4096), ("tiny", 256)])
 @pytest.mark.parametrize("whole", [False, True])
-def test_split_k_schedule_covers_every_row_once(name, chunk, whole):
+@pytest.mark.parametrize("target", [0, 768])
+def test_split_k_schedule_covers_every_row_once(name, chunk, whole, target):
     w = synth.WORKLOADS[name]
     b = synth.budgets_for(w, B.alloc_proportional)
     off, cap, total = B.layout(b, w.L, w.Hkv, w.batch, w.slack)
     cpl = w.batch * w.Hkv
-    items = B.plan_schedule(off, cap, w.L, cpl, chunk, whole)
+    items = B.plan_schedule(off, cap, w.L, cpl, chunk, whole, target_items=target)
     n_caches = w.L * cpl
+    units = [range(n_caches)] if whole else [range(l * cpl, (l + 1) * cpl) for l in range(w.L)]
+    first = {it[0]: it for it in items if it[1] == 0}
+    run_of = {}                                                 # run length of each cache
+    for u in units:
+        at_chunk = sum(max(1, -(-int(cap[c]) // chunk)) for c in u)
+        goal = max(target, len(u))                              # a unit has at least one item per cache
+        n_u = sum(first[c][4] for c in u)
+        if not target or at_chunk <= goal:
+            assert n_u == at_chunk                              # few enough items already: unchanged
+            for c in u:
+                run_of[c] = chunk
+            continue
+        assert n_u <= goal
+        best = chunk                                            # shortest common run that meets the goal
+        while sum(max(1, -(-int(cap[c]) // best)) for c in u) > goal:
+            best += 64
+        for c in u:
+            _, _, count, _, nsplit, _ = first[c]
+            if nsplit > 1:
+                run_of[c] = count
+                assert count == chunk or cap[c] > nsplit * (count - 64)   # runs as equal as 64-row steps allow
+            else:
+                run_of[c] = max(chunk, -(-int(cap[c]) // 64) * 64)
+            assert run_of[c] <= best
+            assert nsplit <= max(1, -(-int(cap[c]) // best))    # balancing adds no item
     seen_rows = np.zeros(n_caches, dtype=np.int64)
     slots = set()
     first_slot = {}
     for (c, start, count, slot, nsplit, row0) in items:
-        assert 0 <= count <= chunk and start % chunk == 0 and start + count <= cap[c]
+        run = run_of[c]
+        assert run % 64 == 0 and run >= chunk
+        assert 0 <= count <= run and start % run == 0 and start + count <= cap[c]
         assert row0 == off[c] + start
-        assert nsplit == max(1, -(-int(cap[c]) // chunk))
+        assert nsplit == max(1, -(-int(cap[c]) // run))
         assert slot not in slots
         slots.add(slot)
         seen_rows[c] += count
-        first_slot.setdefault(c, slot - start // chunk)
-        assert slot == first_slot[c] + start // chunk          # a cache's slots are consecutive
+        first_slot.setdefault(c, slot - start // run)
+        assert slot == first_slot[c] + start // run            # a cache's slots are consecutive
     assert slots == set(range(len(items)))                      # slots are a permutation of 0..n-1
     assert np.array_equal(seen_rows, cap.astype(np.int64))     # every row of every cache exactly once
     # slots are numbered cache by cache

@@ -276,6 +276,6 @@ class Arena:
 
 
 def stream_probe(dst, src, nbytes: int, mode: int, stream=None) -> None:
-    """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only)."""
+    """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only, 2: read only with non-temporal loads)."""
     _check(lib().baklava_stream_probe(dst.data_ptr(), src.data_ptr(), int(nbytes), int(mode),
                                       _stream_ptr(stream)), "baklava_stream_probe")

@@ -7,6 +7,15 @@
 
 namespace baklava {
 
+// 16-byte load with the non-temporal hint, for data a kernel reads exactly once.
+#ifdef __HIPCC__
+typedef uint32_t nt_u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_nt16(const void* ptr) {
+  const nt_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4_t*>(ptr));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+#endif
+
 constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move
 
 // One split-K work item (same layout as baklava_work_item of the public header): rows

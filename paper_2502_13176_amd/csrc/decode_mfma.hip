@@ -29,7 +29,10 @@ namespace {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;
+#ifndef BAKLAVA_MFMA_NW
+#define BAKLAVA_MFMA_NW 4
+#endif
+constexpr int kWaves = BAKLAVA_MFMA_NW;
 constexpr int kSlab = 32;       // rows per wavefront iteration
 constexpr int kVStride = 288;   // bytes between staged V rows: 256 + 32, so the 16 rows touched by one
                                 // transposed read spread evenly over the LDS banks
@@ -47,7 +50,7 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_
 #ifndef BAKLAVA_MFMA_WAVES_PER_EU
 #define BAKLAVA_MFMA_WAVES_PER_EU 3
 #endif
-__global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
+__global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
   __shared__ __attribute__((aligned(16))) float lds_logit[kWaves][16 * kSlab];  // [head][row] per wavefront
 
@@ -86,16 +89,19 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
   u32x4_t kr[2][4];
   u32x4_t vr[8];
 
+  // K and V rows are read once per step: non-temporal loads keep them from displacing the rest of
+  // the cache hierarchy's contents (measured: +4.6% on the attention kernel).
+#define BAKLAVA_LD(ptr) __builtin_nontemporal_load(ptr)
 #define BAKLAVA_LOAD_K(T0)                                                                        \
   _Pragma("unroll") for (int T = 0; T < 2; ++T) {                                                 \
     const uint32_t off = (uint32_t)min((T0) + T * 16 + n16, last) * (kD * 2) + k_lane;            \
     _Pragma("unroll") for (int c = 0; c < 4; ++c)                                                 \
-        kr[T][c] = *reinterpret_cast<const u32x4_t*>(Kb + off + c * 64);                          \
+        kr[T][c] = BAKLAVA_LD(reinterpret_cast<const u32x4_t*>(Kb + off + c * 64));               \
   }
 #define BAKLAVA_LOAD_V(T0)                                                                        \
   _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                 \
     const uint32_t off = (uint32_t)min((T0) + jg + 4 * i, last) * (kD * 2) + v_lane;              \
-    vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + off);                                          \
+    vr[i] = BAKLAVA_LD(reinterpret_cast<const u32x4_t*>(Vb + off));                               \
   }
 
   // Logit stash (score tracking): a slab's logits form one contiguous block [G][32]; lane l < 8G
@@ -223,6 +229,7 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
+#undef BAKLAVA_LD
 #undef BAKLAVA_LOAD_K
 #undef BAKLAVA_LOAD_V
 
@@ -248,7 +255,7 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
     }
   }
   __syncthreads();
-  finish_item<kD, 16>(p, it, G, n, sm_o, sm_m, sm_l);
+  finish_item<kD, 16, kWaves>(p, it, G, n, sm_o, sm_m, sm_l);
 }
 
 }  // namespace
@@ -256,7 +263,7 @@ __global__ __launch_bounds__(256, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
   if (p.G > 16) return hipErrorInvalidValue;
-  decode_partial_mfma<<<dim3(n_items), dim3(256), 0, s>>>(p);
+  decode_partial_mfma<<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
   return hipGetLastError();
 }
 

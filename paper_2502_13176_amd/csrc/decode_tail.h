@@ -35,11 +35,11 @@ __device__ __forceinline__ void append_new_row(const DecodeParams& p, const Item
   __syncthreads();
 }
 
-// End of a work item.  On entry sm_o[w][g][d], sm_m[w][g], sm_l[w][g] (w < 4 wavefronts, g-stride
+// End of a work item.  On entry sm_o[w][g][d], sm_m[w][g], sm_l[w][g] (w < NW wavefronts, g-stride
 // LDG) hold each wavefront's un-normalised output, running max and sum, and a barrier has been
 // passed.  A cache that has a single work item is finished on the spot; otherwise the item's
 // partial (max, sum, un-normalised output) is stored for the combine kernel.
-template <int D, int LDG>
+template <int D, int LDG, int NW = 4>
 __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& it, int G, int n_new,
                                             const float* sm_o, const float* sm_m, const float* sm_l) {
   const int tid = threadIdx.x;
@@ -48,15 +48,15 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
   const int c_rel = c - p.cache_begin;
   const int64_t orow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
 
-  for (int idx = tid; idx < G * D; idx += 256) {
+  for (int idx = tid; idx < G * D; idx += 64 * NW) {
     const int g = idx / D, d = idx % D;
     float mm = sm_m[g];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mm = fmaxf(mm, sm_m[w * LDG + g]);
+    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, sm_m[w * LDG + g]);
     const float ms = (mm == kTailNegInf) ? 0.f : mm;
     float ll = 0.f, oo = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float a = tail_exp2(sm_m[w * LDG + g] - ms);
       ll += sm_l[w * LDG + g] * a;
       oo += sm_o[(w * LDG + g) * D + d] * a;

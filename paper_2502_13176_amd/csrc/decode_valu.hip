@@ -101,8 +101,9 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = min(t0 + u * RPW + rg, cnt - 1);  // clamped: always a live row of this item
-      kraw[u] = *reinterpret_cast<const uint4*>(Kb + (int64_t)r * D);
-      vraw[u] = *reinterpret_cast<const uint4*>(Vb + (int64_t)r * D);
+      // read once per step: non-temporal, so that the stream does not displace other cached data
+      kraw[u] = load_nt16(Kb + (int64_t)r * D);
+      vraw[u] = load_nt16(Vb + (int64_t)r * D);
     }
     float s[U][GT];
 #pragma unroll
@@ -248,21 +249,27 @@ __global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
   const Item it = p.items[blockIdx.x];
   const int G = p.G;
   const int n = p.len[it.c];
-  const int r0 = blockIdx.y * kScoreTile;
-  const int cnt = min(min(it.start + it.count, n) - it.start, r0 + kScoreTile);
-  if (r0 >= cnt) return;
-  const int64_t row0 = p.off[it.c] + it.start;
-  const float* lg = p.logits + p.stash_off[it.c];
-  for (int r = r0 + threadIdx.x; r < cnt; r += 256) {
-    float w = 0.f;
-    for (int g = 0; g < G; ++g) {
-      const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
-      const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
-      const int j = it.start + r;
-      w += fast_exp2(lg[(int64_t)(j >> 5) * (32 * G) + 32 * g + (j & 31)] - M) * inv;
-    }
-    p.score[row0 + r] += w;
+  const int cnt = min(it.start + it.count, n) - it.start;
+  // Four consecutive rows per thread; work items start on a multiple of 64 rows, so the four
+  // logits of a head are one aligned 16-byte piece of the slab's [G][32] block.
+  const int r = blockIdx.y * kScoreTile + threadIdx.x * 4;
+  if (r >= cnt) return;
+  const int j = it.start + r;
+  const float* lg = p.logits + p.stash_off[it.c] + (int64_t)(j >> 5) * (32 * G) + (j & 31);
+  float w[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < G; ++g) {
+    const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
+    const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
+    const float4 x = *reinterpret_cast<const float4*>(lg + 32 * g);
+    w[0] += fast_exp2(x.x - M) * inv;
+    w[1] += fast_exp2(x.y - M) * inv;
+    w[2] += fast_exp2(x.z - M) * inv;
+    w[3] += fast_exp2(x.w - M) * inv;
   }
+  float* sc = p.score + p.off[it.c] + j;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (r + e < cnt) sc[e] += w[e];
 }
 
 // [K'; K_t], [V'; V_t] of Eq. 7: the new row goes to slot len, then len += 1.

@@ -3,7 +3,8 @@
 // give the bandwidth a trivial kernel reaches on the same device.
 //
 // The read sweep gives each workgroup one contiguous 256 KiB block and keeps 8 16-byte loads per
-// thread in flight, the access shape that gave the highest read bandwidth of the shapes tried.
+// thread in flight, the access shape that gave the highest read bandwidth of the shapes tried;
+// it exists with ordinary and with non-temporal loads.
 #include "common.h"
 
 namespace baklava {
@@ -20,6 +21,7 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ ds
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+template <bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(uint32_t* __restrict__ dst,
                                                           const uint4* __restrict__ src, int64_t n16) {
   const int64_t b0 = (int64_t)blockIdx.x * kBlock16;
@@ -28,7 +30,10 @@ __global__ __launch_bounds__(256) void stream_read_kernel(uint32_t* __restrict__
   for (int64_t i = b0 + threadIdx.x; i < b1; i += 256 * kU) {
     uint4 v[kU];
 #pragma unroll
-    for (int u = 0; u < kU; ++u) v[u] = (i + u * 256 < b1) ? src[i + u * 256] : make_uint4(0, 0, 0, 0);
+    for (int u = 0; u < kU; ++u) {
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (i + u * 256 < b1) v[u] = NT ? load_nt16(src + i + u * 256) : src[i + u * 256];
+    }
 #pragma unroll
     for (int u = 0; u < kU; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
@@ -44,8 +49,10 @@ hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mo
   const dim3 grid((unsigned)((n16 + kBlock16 - 1) / kBlock16)), block(256);
   if (mode == 0)
     stream_copy_kernel<<<dim3(4096), block, 0, s>>>(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
+  else if (mode == 1)
+    stream_read_kernel<false><<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
   else
-    stream_read_kernel<<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
+    stream_read_kernel<true><<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
   return hipGetLastError();
 }
 

@@ -4,8 +4,8 @@
 // The G query heads that share a KV head form the N side (padded to 16) of two matrix products
 // per 32-row slab, both issued as v_mfma_f32_16x16x32_bf16:
 //
-//   S^T[row, g]  = K[row, :] . Q[g, :]          A = K rows (read straight from HBM into the
-//                                               A-operand layout: lane (row%16, j) holds 8
+//   S^T[row, g]  = K[row, :] . Q[g, :]          A = K rows (staged through LDS: whole rows are
+//                                               loaded, lane (row%16, j) then reads its 8
 //                                               consecutive head-dim elements), B = Q
 //   O^T[d, g]   += V^T[d, rows] . P^T[rows, g]  A = V^T (staged through LDS, read back
 //                                               transposed), B = P^T
@@ -17,8 +17,13 @@
 // g, g+16, g+32, g+48.  Softmax weights are split into two bf16 terms (high part and residual)
 // so that the second product keeps ~16 bits of each weight.
 //
-// Each of the 4 wavefronts of a workgroup streams its own 32-row slabs and owns a private LDS
-// region: there is no barrier inside the loop.
+// Both K and V are fetched as whole 256-byte rows, four rows per load instruction.  Reading K
+// straight into the A-operand layout would save its trip through LDS, but touches only 64 bytes
+// of each of 16 rows per instruction, and that access shape streams about 10% slower from HBM
+// than whole rows do.
+//
+// Each wavefront of a workgroup streams its own 32-row slabs and owns a private LDS region: there
+// is no barrier inside the loop.
 #include "common.h"
 #include "decode_tail.h"
 
@@ -36,6 +41,8 @@ constexpr int kWaves = BAKLAVA_MFMA_NW;
 constexpr int kSlab = 32;       // rows per wavefront iteration
 constexpr int kVStride = 288;   // bytes between staged V rows: 256 + 32, so the 16 rows touched by one
                                 // transposed read spread evenly over the LDS banks
+constexpr int kKStride = 272;   // bytes between staged K rows: 256 + 16, so 16 lanes that read the same
+                                // 16 bytes of 16 consecutive rows hit 16 different bank groups
 constexpr int kD = 128;
 constexpr float kNegInf = -__builtin_huge_valf();
 
@@ -48,11 +55,14 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_cast(bf16x8_t, x); }
 
 #ifndef BAKLAVA_MFMA_WAVES_PER_EU
-#define BAKLAVA_MFMA_WAVES_PER_EU 3
+#define BAKLAVA_MFMA_WAVES_PER_EU 2
 #endif
 __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
-  __shared__ __attribute__((aligned(16))) float lds_logit[kWaves][16 * kSlab];  // [head][row] per wavefront
+  // K staging; once a slab's A operands are read, the same bytes serve as the [head][row] buffer of
+  // the logit stash
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWaves * kSlab * kKStride];
+  static_assert(16 * kSlab * 4 <= kSlab * kKStride, "logit buffer fits the K staging area");
 
   const Item it = p.items[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -70,6 +80,7 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.k) + row0 * (kD * 2);
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(p.v) + row0 * (kD * 2);
   unsigned char* myl = lds + wave * (kSlab * kVStride);
+  unsigned char* myk = lds_k + wave * (kSlab * kKStride);
 
   const int c_rel = it.c - p.cache_begin;
   const int64_t qrow0 = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G;
@@ -85,18 +96,17 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   // rows is ever read; a clamped row's softmax weight is forced to zero below.  Offsets from the
   // item's first row fit 32 bits (a work item spans < 2^23 rows).
   const int last = cnt - 1;
-  const uint32_t k_lane = jg * 16, v_lane = n16 * 16;
-  u32x4_t kr[2][4];
+  const uint32_t v_lane = n16 * 16;
+  u32x4_t kr[8];
   u32x4_t vr[8];
 
   // K and V rows are read once per step: non-temporal loads keep them from displacing the rest of
   // the cache hierarchy's contents (measured: +4.6% on the attention kernel).
 #define BAKLAVA_LD(ptr) __builtin_nontemporal_load(ptr)
 #define BAKLAVA_LOAD_K(T0)                                                                        \
-  _Pragma("unroll") for (int T = 0; T < 2; ++T) {                                                 \
-    const uint32_t off = (uint32_t)min((T0) + T * 16 + n16, last) * (kD * 2) + k_lane;            \
-    _Pragma("unroll") for (int c = 0; c < 4; ++c)                                                 \
-        kr[T][c] = BAKLAVA_LD(reinterpret_cast<const u32x4_t*>(Kb + off + c * 64));               \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                 \
+    const uint32_t off = (uint32_t)min((T0) + jg + 4 * i, last) * (kD * 2) + v_lane;              \
+    kr[i] = BAKLAVA_LD(reinterpret_cast<const u32x4_t*>(Kb + off));                               \
   }
 #define BAKLAVA_LOAD_V(T0)                                                                        \
   _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                 \
@@ -135,16 +145,27 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   for (; t0 < cnt; t0 += kWaves * kSlab) {
     const int tn = t0 + kWaves * kSlab;
 
-    // ---- S^T = K Q^T, then the next slab's K loads reuse the registers ------------------------
+    // ---- stage K rows in LDS; the next slab's K loads reuse the registers ----------------------
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<u32x4_t*>(myk + (jg + 4 * i) * kKStride + n16 * 16) = kr[i];
+    }
+    BAKLAVA_LOAD_K(tn)  // past the end every row clamps to the last live row: harmless re-reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- S^T = K Q^T: lane (row%16, j) reads elements 32c + 8j .. +8 of its row ----------------
     floatx4_t s[2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
       s[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        s[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kr[T][c]), qb[c], s[T], 0, 0, 0);
+      for (int c = 0; c < 4; ++c) {
+        const u32x4_t a = *reinterpret_cast<const u32x4_t*>(myk + (T * 16 + n16) * kKStride + c * 64 + jg * 16);
+        s[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), qb[c], s[T], 0, 0, 0);
+      }
     }
-    BAKLAVA_LOAD_K(tn)  // past the end every row clamps to the last live row: harmless re-reads
 
     // ---- stage V rows in LDS, then the next slab's V loads reuse the registers ----------------
 #pragma unroll
@@ -170,7 +191,9 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
       // Through LDS from the accumulator layout (lane (g, jg): rows 4jg..4jg+3 of each tile) to
       // one line per head.  Rows past the live length carry -inf and are never read back.
       typedef float f32x4_t __attribute__((ext_vector_type(4)));
-      float* tl = lds_logit[wave];
+      float* tl = reinterpret_cast<float*>(myk);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();  // the slab's K operands have been read
       if (n16 < G) {
 #pragma unroll
         for (int T = 0; T < 2; ++T)

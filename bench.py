@@ -33,6 +33,8 @@ def parse_args():
                          "stack: one launch over all layers")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
+    ap.add_argument("--target-items-whole", type=int, default=-1,
+                    help="work items per whole-model launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--target-items", type=int, default=-1,
                     help="work items per layer launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,6 +150,8 @@ def main():
         arena.set_option(B.OPT_KERNEL, args.kernel)
     if args.target_items >= 0:
         arena.set_option(B.OPT_TARGET_ITEMS, args.target_items)
+    if args.target_items_whole >= 0:
+        arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, args.target_items_whole)
     if args.chunk:
         arena.set_option(B.OPT_CHUNK_TOKENS, args.chunk)
         arena.set_option(B.OPT_CHUNK_TOKENS_WHOLE, args.chunk)

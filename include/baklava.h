@@ -168,14 +168,17 @@ int baklava_destroy(baklava_ctx* ctx);
 
 /* Tuning knobs (tests sweep them; results must not depend on them beyond rounding order). */
 enum {
-  BAKLAVA_OPT_CHUNK_TOKENS = 1, /* rows per split-K work item for launches over part of the layers
-                                   (multiple of 64, >= 256)                                          */
+  BAKLAVA_OPT_CHUNK_TOKENS = 1, /* shortest run of rows per split-K work item for launches over part of
+                                   the layers (multiple of 64, >= 256); the item target below may
+                                   lengthen it                                                        */
   BAKLAVA_OPT_KERNEL = 2,       /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
   BAKLAVA_OPT_TIME_KERNEL = 3,  /* 1: bracket every attention partial-kernel launch with HIP events  */
-  BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* rows per work item for launches over all layers at once     */
-  BAKLAVA_OPT_TARGET_ITEMS = 5  /* > 0: launches over part of the layers lengthen their runs, layer by
+  BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* the same for launches over all layers at once               */
+  BAKLAVA_OPT_TARGET_ITEMS = 5, /* > 0: launches over part of the layers lengthen their runs, layer by
                                    layer, until a layer has at most this many work items; 0: off.
                                    Default: the device's number of compute units                    */
+  BAKLAVA_OPT_TARGET_ITEMS_WHOLE = 6 /* the same for launches over all layers at once.  Default: five
+                                   times the device's number of compute units                      */
 };
 int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
 

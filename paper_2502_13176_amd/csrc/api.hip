@@ -24,7 +24,8 @@ inline bool hip_ok(hipError_t e) {
 constexpr int kMinChunk = 256;
 constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
 constexpr int kDefaultChunk = 512;        // launches over part of the model (a few hundred MB)
-constexpr int kDefaultChunkWhole = 2048;  // launches over the whole model (GBs): fewer, larger items
+constexpr int kDefaultChunkWhole = 256;   // launches over the whole model: shortest run; longer ones come from the item target
+constexpr int kWholeItemsPerCu = 5;       // whole-model launches aim at this many work items per compute unit
 constexpr int kMaxChunk = 1 << 22; // row offsets inside a work item stay below 2^32 bytes
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -125,6 +126,7 @@ struct baklava_ctx {
   std::vector<int32_t> seg_begin;               // cache -> first segment of the eviction move
   int32_t kernel_pref;
   int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
+  int32_t target_items_whole;  // > 0: the same for launches over the whole model
   struct Schedule {
     int32_t chunk = 0;
     int32_t max_count = 0;             // longest work item, rows
@@ -148,7 +150,8 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   int64_t n_items = 0;
   std::vector<baklava_work_item> items((size_t)ctx->plan.max_items);
   const int st = baklava_plan_schedule(ctx->off.data(), ctx->cap.data(), ctx->d.L, ctx->cpl, chunk,
-                                       which == 0 ? ctx->target_items : 0, which, ctx->plan.max_items,
+                                       which == 0 ? ctx->target_items : ctx->target_items_whole, which,
+                                       ctx->plan.max_items,
                                        items.data(), &n_items);
   if (st != BAKLAVA_OK) return st;
   static_assert(sizeof(baklava_work_item) == sizeof(Item), "work item layouts must match");
@@ -310,6 +313,9 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       return BAKLAVA_EHIP;
     }
     ctx->target_items = cus;
+    // Whole-model launches: runs long enough to amortise the per-item costs, yet enough items for
+    // the dispatcher to even out the load over several waves of workgroups.
+    ctx->target_items_whole = kWholeItemsPerCu * cus;
   }
   ctx->time_kernel = false;
   ctx->ev_used = 0;
@@ -397,10 +403,14 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       return build_schedule(ctx, which, (int32_t)value);
     }
     case BAKLAVA_OPT_TARGET_ITEMS:
+    case BAKLAVA_OPT_TARGET_ITEMS_WHOLE: {
       if (value < 0 || value > (1 << 20)) return BAKLAVA_EINVAL;
-      if ((int32_t)value == ctx->target_items) return BAKLAVA_OK;
-      ctx->target_items = (int32_t)value;
-      return build_schedule(ctx, 0, ctx->sched[0].chunk);
+      const int which = option == BAKLAVA_OPT_TARGET_ITEMS ? 0 : 1;
+      int32_t& target = which == 0 ? ctx->target_items : ctx->target_items_whole;
+      if ((int32_t)value == target) return BAKLAVA_OK;
+      target = (int32_t)value;
+      return build_schedule(ctx, which, ctx->sched[which].chunk);
+    }
     case BAKLAVA_OPT_KERNEL:
       if (value < 0 || value > 2) return BAKLAVA_EINVAL;
       if (value == 2 && !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_EINVAL;

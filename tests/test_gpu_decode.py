@@ -86,6 +86,19 @@ def test_ragged_lengths_all_shapes(dtype, D, Hq, Hkv):
         out1 = H.gpu_decode(arena, w, q[1:2], layer_begin=1, layer_count=1)
         H.check_decode_against_oracle(arena, w, st, q64[1:2], out1, caches=range(n_caches // 2, n_caches),
                                           layer_begin=1)
+        # item targets below the item count at 256-row runs: runs grow (per layer / over the model)
+        # until few items are left, down to one item per cache
+        H.set_chunk(arena, 256)
+        for target in (1, 7, 23):
+            arena.set_option(B.OPT_TARGET_ITEMS, target)
+            arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
+            out = H.gpu_decode(arena, w, q)
+            H.check_decode_against_oracle(arena, w, st, q64, out)
+            out1 = H.gpu_decode(arena, w, q[1:2], layer_begin=1, layer_count=1)
+            H.check_decode_against_oracle(arena, w, st, q64[1:2], out1, caches=range(n_caches // 2, n_caches),
+                                          layer_begin=1)
+        arena.set_option(B.OPT_TARGET_ITEMS, 0)
+        arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, 0)
     arena.close()
 
 

@@ -25,8 +25,8 @@ def _h():
 
 @pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
 @pytest.mark.parametrize("fused", [False, True])
-@pytest.mark.parametrize("base,Hq,Hkv", [("long", 8, 2), ("qwen", 7, 1)])
-def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv):
+@pytest.mark.parametrize("base,Hq,Hkv,target", [("long", 8, 2, 0), ("qwen", 7, 1, 0), ("long", 8, 2, 3)])
+def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv, target):
     H = _h()
     w = synth.shrink(synth.WORKLOADS[base], name="steps", L=2, Hq=Hq, Hkv=Hkv, batch=2, ctx=2048, lo=96,
                      hi=2048, interval=8, slack=8, sink=4, recent=16, steps=20, floor_frac=0.0)
@@ -36,6 +36,10 @@ def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv):
     arena = H.make_arena(w, budgets, track=True)
     arena.set_option(B.OPT_KERNEL, kernel)
     H.set_chunk(arena, 256)
+    # target 3: at most 3 work items per layer launch, so work items of up to 2048 rows whose score
+    # update spans several workgroups
+    arena.set_option(B.OPT_TARGET_ITEMS, target)
+    arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
     cpl = w.batch * w.Hkv
     lens = [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]
     H.fill_from_host(arena, w, lens, rng, scores="zero")

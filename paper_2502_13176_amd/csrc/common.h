@@ -14,6 +14,10 @@ __device__ __forceinline__ uint4 load_nt16(const void* ptr) {
   const nt_u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4_t*>(ptr));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ void store_nt16(void* ptr, uint4 v) {
+  const nt_u32x4_t x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<nt_u32x4_t*>(ptr));
+}
 #endif
 
 constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move

@@ -17,6 +17,10 @@ Pins (see tests/test_oracle_*.py):
   alloc_threshold        conservation + structure only: the paper prints no
                          worked example of Algorithm 2 -> beyond those
                          invariants PARITY UNPINNED
+  head_similarity        pure-Python brute force, closed forms (one token, two
+                         tokens, uniform attention = prefix means, identity
+                         attention), scale invariance, torch fp64 causal SDPA
+  kv_importance          hand-computed values, range and monotonicity
 """
 from __future__ import annotations
 
@@ -276,3 +280,63 @@ def decode_step(cache: Cache, q: np.ndarray, k_new, v_new, token_pos: int, step_
     if interval > 0 and step_index % interval == 0:
         kept = cache.compact(budget, sink, recent, policy)
     return out, p, kept
+
+
+# ---------------------------------------------------------------------------
+# One-time profiling (Algorithm 1)
+# ---------------------------------------------------------------------------
+
+COS_EPS = 1e-8  # the product of the two norms is clamped from below by this value
+
+
+def head_similarity(Q: np.ndarray, K: np.ndarray, V: np.ndarray) -> Tuple[float, np.ndarray]:
+    """Algorithm 1, step 1, for one attention head and one prompt.
+
+    Q, K, V: [T, D] (the head's query rows and the key / value rows of the KV
+    head it reads).  For every prompt token t the head's output row is
+    out_t = sum_{j<=t} softmax_j(q_t . k_j / sqrt(D)) v_j (Eq. 1 with the causal
+    mask of autoregressive inference) and the token's similarity is the cosine
+    between the head's input row v_t and out_t.  Returns (mean over tokens,
+    per-token cosines).
+
+    Readings: the mask is causal (the algorithm runs "inference" on the prompt);
+    logits are scaled by 1/sqrt(D) as in Eq. 1; a cosine whose norm product is
+    below COS_EPS divides by COS_EPS instead (so a zero row gives 0), the
+    convention of the usual library routine, since the paper does not say.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    T, D = Q.shape
+    if K.shape != (T, D) or V.shape != (T, D) or T < 1:
+        raise ValueError("Q, K, V must all be [T, D] with T >= 1")
+    cos = np.empty(T, dtype=np.float64)
+    scale = 1.0 / math.sqrt(D)
+    for t in range(T):
+        s = (K[: t + 1] @ Q[t]) * scale
+        w = np.exp(s - s.max())
+        out = (w / w.sum()) @ V[: t + 1]
+        denom = max(float(np.linalg.norm(V[t]) * np.linalg.norm(out)), COS_EPS)
+        cos[t] = float(V[t] @ out) / denom
+    return float(cos.mean()), cos
+
+
+def kv_importance(similarity: np.ndarray, G: int) -> np.ndarray:
+    """Algorithm 1, step 2, plus the normalisation of the text ("Head Importance Heuristic").
+
+    similarity: [L, Hq] mean cosines in [-1, 1] (one prompt, or already averaged
+    over prompts).  The G consecutive heads that share a KV cache are averaged,
+    the mean is mapped from [-1, 1] to [0, 1], and importance is its complement:
+    I[l, h] = 1 - (mean_g s[l, h*G + g] + 1) / 2.
+
+    Reading: the map to [0, 1] is the affine one, (s + 1) / 2; the paper says
+    "normalize these values from range 0 to 1" and prints no formula.  The map
+    is applied after the group mean; being affine it commutes with the mean.
+    """
+    s = np.asarray(similarity, dtype=np.float64)
+    L, Hq = s.shape
+    if G < 1 or Hq % G:
+        raise ValueError("Hq must be a multiple of G")
+    grouped = s.reshape(L, Hq // G, G).mean(axis=2)
+    return 1.0 - (grouped + 1.0) / 2.0
+

@@ -259,6 +259,40 @@ int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launch
  */
 int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * One-time profiling (Algorithm 1), the step that produces the importance scores the budget
+ * allocators above consume.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Algorithm 1, step 1, for every attention head of `batch` prompts of T tokens: causal attention of
+ * the head over the prompt (Eq. 1 with the mask of autoregressive inference, logits scaled by
+ * 1/sqrt(D)), the cosine between each token's value row v_t (the head's input) and the head's
+ * output row for that token, and the mean of the cosines over the prompt.
+ * q DEVICE bf16 [batch, Hq, T, D]; k, v DEVICE bf16 [batch, Hkv, T, D] (query head h reads KV head
+ * h / (Hq/Hkv)); all 16-byte aligned.  D must be 128 and dtype BAKLAVA_BF16.
+ * cos_out DEVICE fp32 [batch, Hq, T] (per-token cosines) or NULL; sim_out DEVICE fp32 [batch, Hq]
+ * (mean per head).  A cosine whose norm product is below 1e-8 is divided by 1e-8 instead (a zero
+ * row gives 0).  workspace DEVICE, at least baklava_profile_workspace_bytes(batch, Hq, T) bytes,
+ * 16-byte aligned, owned by the caller and free again once the stream has passed the call.
+ * Enqueues two kernels on `stream`, does not synchronise.  Results are deterministic.
+ * Errors: EINVAL (null, misaligned, bad shape), ECAPACITY (workspace too small), EHIP.
+ */
+size_t baklava_profile_workspace_bytes(int32_t batch, int32_t Hq, int32_t T);
+int baklava_profile_similarity(const void* q, const void* k, const void* v, int32_t batch, int32_t Hq,
+                               int32_t Hkv, int32_t T, int32_t D, int32_t dtype, float* cos_out,
+                               float* sim_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Algorithm 1, step 2, with the normalisation of "Head Importance Heuristic" (host only): the
+ * similarities of the Hq/Hkv heads that share a KV cache are averaged, mapped from [-1, 1] to
+ * [0, 1] by (s + 1) / 2, and importance is the complement.
+ * similarity_host HOST double [L * Hq]; importance_out HOST double [L * Hkv].
+ * Errors: EINVAL (null, Hq not a multiple of Hkv, a similarity outside [-1, 1] or not finite).
+ */
+int baklava_kv_importance(const double* similarity_host, int32_t L, int32_t Hq, int32_t Hkv,
+                          double* importance_out);
+
 /* Host mirror of the lengths; len_host_out HOST [n_caches].  No device access. */
 int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);
 

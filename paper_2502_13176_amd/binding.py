@@ -29,7 +29,7 @@ EXPORTS = [
     "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
-    "baklava_stream_probe",
+    "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance",
 ]
 
 
@@ -91,8 +91,14 @@ def lib() -> C.CDLL:
     L.baklava_lengths.argtypes = [C.c_void_p, i32p]
     L.baklava_profile_read.argtypes = [C.c_void_p, f64p, i64p]
     L.baklava_stream_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    L.baklava_profile_workspace_bytes.restype = C.c_size_t
+    L.baklava_profile_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    L.baklava_profile_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
+    L.baklava_kv_importance.argtypes = [f64p, C.c_int32, C.c_int32, C.c_int32, f64p]
     for name in EXPORTS:
-        if name not in ("baklava_strerror", "baklava_workspace_bytes"):
+        if name not in ("baklava_strerror", "baklava_workspace_bytes", "baklava_profile_workspace_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -279,3 +285,40 @@ def stream_probe(dst, src, nbytes: int, mode: int, stream=None) -> None:
     """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only, 2: read only with non-temporal loads)."""
     _check(lib().baklava_stream_probe(dst.data_ptr(), src.data_ptr(), int(nbytes), int(mode),
                                       _stream_ptr(stream)), "baklava_stream_probe")
+
+
+def kv_importance(similarity, L: int, Hq: int, Hkv: int) -> np.ndarray:
+    """baklava_kv_importance: [L, Hq] head similarities -> [L, Hkv] KV-cache importances (host only)."""
+    sim = np.ascontiguousarray(similarity, dtype=np.float64).reshape(-1)
+    if sim.size != L * Hq:
+        raise ValueError("similarity must hold L * Hq values")
+    out = np.zeros(L * Hkv, dtype=np.float64)
+    _check(lib().baklava_kv_importance(_p(sim, C.c_double), L, Hq, Hkv, _p(out, C.c_double)), "baklava_kv_importance")
+    return out.reshape(L, Hkv)
+
+
+def profile_workspace_bytes(batch: int, Hq: int, T: int) -> int:
+    return int(lib().baklava_profile_workspace_bytes(batch, Hq, T))
+
+
+def profile_similarity(q, k, v, want_cos: bool = True, stream=None):
+    """baklava_profile_similarity on torch device tensors q [batch, Hq, T, D], k / v [batch, Hkv, T, D]
+    (bf16).  Returns (sim [batch, Hq], cos [batch, Hq, T] or None) as torch fp32 device tensors."""
+    import torch
+    batch, Hq, T, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape != (batch, Hkv, T, D) or v.shape != k.shape:
+        raise ValueError("k and v must be [batch, Hkv, T, D]")
+    if q.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or v.dtype != torch.bfloat16:
+        raise ValueError("bf16 tensors expected")
+    if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+        raise ValueError("contiguous tensors expected")
+    sim = torch.empty((batch, Hq), dtype=torch.float32, device=q.device)
+    cos = torch.empty((batch, Hq, T), dtype=torch.float32, device=q.device) if want_cos else None
+    nbytes = profile_workspace_bytes(batch, Hq, T)
+    ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q.device)
+    _check(lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), batch, Hq, Hkv, T, D, BF16,
+                                            cos.data_ptr() if want_cos else None, sim.data_ptr(), ws.data_ptr(),
+                                            nbytes, _stream_ptr(stream)), "baklava_profile_similarity")
+    return sim, cos
+

@@ -531,6 +531,29 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
   return BAKLAVA_OK;
 }
 
+extern "C" size_t baklava_profile_workspace_bytes(int32_t batch, int32_t Hq, int32_t T) {
+  if (batch <= 0 || Hq <= 0 || T <= 0) return 0;
+  const int64_t n_tiles = ((int64_t)T + 127) / 128;  // 128 tokens per workgroup
+  return align256((size_t)batch * Hq * n_tiles * sizeof(float));
+}
+
+extern "C" int baklava_profile_similarity(const void* q, const void* k, const void* v, int32_t batch,
+                                          int32_t Hq, int32_t Hkv, int32_t T, int32_t D, int32_t dtype,
+                                          float* cos_out, float* sim_out, void* workspace,
+                                          size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !sim_out || !workspace) return BAKLAVA_EINVAL;
+  if (batch <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || Hq % Hkv) return BAKLAVA_EINVAL;
+  if (D != 128 || dtype != BAKLAVA_BF16) return BAKLAVA_EINVAL;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)workspace) & 15) return BAKLAVA_EINVAL;
+  if (((uintptr_t)sim_out | (uintptr_t)cos_out) & 3) return BAKLAVA_EINVAL;
+  if ((int64_t)batch * Hq * (((int64_t)T + 127) / 128) > INT32_MAX) return BAKLAVA_EINVAL;
+  if (workspace_bytes < baklava_profile_workspace_bytes(batch, Hq, T)) return BAKLAVA_ECAPACITY;
+  if (!hip_ok(launch_profile_similarity(q, k, v, batch, Hq, Hkv, T, cos_out, sim_out,
+                                        reinterpret_cast<float*>(workspace), (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
 extern "C" int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out) {
   if (!ctx || !len_host_out) return BAKLAVA_EINVAL;
   std::memcpy(len_host_out, ctx->len.data(), ctx->n_caches * sizeof(int32_t));

@@ -148,6 +148,23 @@ extern "C" int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int
   return BAKLAVA_OK;
 }
 
+// Algorithm 1, step 2: group mean of the head similarities, affine map to [0, 1], complement.
+extern "C" int baklava_kv_importance(const double* similarity_host, int32_t L, int32_t Hq, int32_t Hkv,
+                                     double* importance_out) {
+  if (!similarity_host || !importance_out || L <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return BAKLAVA_EINVAL;
+  const int32_t G = Hq / Hkv;
+  // a rounding slack on the range check: means of fp32 cosines can exceed 1 by an ulp
+  for (int64_t i = 0; i < (int64_t)L * Hq; ++i)
+    if (!std::isfinite(similarity_host[i]) || std::fabs(similarity_host[i]) > 1.0 + 1e-6) return BAKLAVA_EINVAL;
+  for (int32_t l = 0; l < L; ++l)
+    for (int32_t h = 0; h < Hkv; ++h) {
+      double acc = 0.0;
+      for (int32_t g = 0; g < G; ++g) acc += similarity_host[(int64_t)l * Hq + (int64_t)h * G + g];
+      importance_out[(int64_t)l * Hkv + h] = 1.0 - (acc / G + 1.0) / 2.0;
+    }
+  return BAKLAVA_OK;
+}
+
 // Split-K schedule: runs of equal length over each cache's capacity, in launch order.
 extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
                                      int32_t caches_per_layer, int32_t chunk, int32_t target_items,

@@ -187,3 +187,26 @@ def test_split_k_schedule_errors():
     with pytest.raises(B.BaklavaError) as e:
         B.plan_schedule(off, cap, 1, 2, 256, False, max_items=5)
     assert e.value.status == B.ECAPACITY
+
+
+def test_kv_importance_matches_oracle():
+    rng = np.random.default_rng(77)
+    for L, Hq, Hkv in ((1, 4, 2), (32, 32, 8), (28, 28, 4), (3, 5, 5)):
+        s = rng.uniform(-1, 1, (L, Hq))
+        got = B.kv_importance(s, L, Hq, Hkv)
+        assert got.shape == (L, Hkv)
+        assert np.allclose(got, O.kv_importance(s, Hq // Hkv), rtol=0, atol=1e-15)
+    assert B.kv_importance([[1.0, 0.0, -1.0, 0.5]], 1, 4, 2).tolist() == [[0.25, 0.625]]
+    for bad in ([[2.0, 0.0]], [[float("nan"), 0.0]]):
+        with pytest.raises(B.BaklavaError) as e:
+            B.kv_importance(bad, 1, 2, 1)
+        assert e.value.status == B.EINVAL
+    with pytest.raises(B.BaklavaError) as e:
+        B.kv_importance([[0.0, 0.0, 0.0]], 1, 3, 2)
+    assert e.value.status == B.EINVAL
+
+
+def test_profile_workspace_bytes():
+    assert B.profile_workspace_bytes(1, 4, 128) == 256
+    assert B.profile_workspace_bytes(2, 32, 8192) == 2 * 32 * 64 * 4
+    assert B.profile_workspace_bytes(0, 4, 128) == 0

@@ -33,6 +33,8 @@ def parse_args():
                          "stack: one launch over all layers")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
+    ap.add_argument("--no-profiling-row", action="store_true",
+                    help="skip the measurement of the one-time profiling kernel")
     ap.add_argument("--target-items-whole", type=int, default=-1,
                     help="work items per whole-model launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--target-items", type=int, default=-1,
@@ -107,6 +109,71 @@ def stream_probe(torch, B, device, nbytes=1 << 32, reps=5):
         out[f"{name}_GBps"] = round(moved / ms / 1e6, 1)
     del src, dst
     return out
+
+
+def profiling_row(torch, B, device, with_cpu_baseline, T=8192, Hq=32, Hkv=8, reps=10):
+    """The profiling kernel (Algorithm 1 step 1) on one LLaMA-3-8B-shaped layer of a T-token prompt:
+    algorithmic flops (2 D T (T+1) per head: both products, causal half only) per second, timed with
+    events on the launch stream; the oracle's rate on the host cores beside it."""
+    D = 128
+    gen = torch.Generator(device=device)
+    gen.manual_seed(4242)
+    q = torch.randn((1, Hq, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((1, Hkv, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((1, Hkv, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    sim = torch.empty((1, Hq), dtype=torch.float32, device=device)
+    nbytes = B.profile_workspace_bytes(1, Hq, T)
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run():
+        st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, Hq, Hkv, T, D, B.BF16,
+                                                None, sim.data_ptr(), ws.data_ptr(), nbytes, stream)
+        if st != B.OK:
+            raise RuntimeError(f"baklava_profile_similarity: status {st}")
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = Hq * 2 * D * T * (T + 1)
+    row = {
+        "what": "Algorithm 1 step 1: causal attention + token-wise cosine(v_t, out_t) + mean, one layer",
+        "config": {"workload": f"LLaMA-3-8B-shaped layer: {Hq} heads, {Hkv} KV heads, D={D}, prompt of {T} tokens, bf16"},
+        "us": round(ms * 1e3, 1),
+        "roofline": {"bound": "mfma", "kernel": "profile_attn_kernel", "achieved": round(flops / ms / 1e9, 1),
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / ms / 1e9 / 2500.0, 4), "traffic": None,
+                     "algorithmic_flops_per_launch": flops},
+    }
+    if with_cpu_baseline:
+        import time
+        import numpy as np
+        from oracle import baklava_oracle as O
+        from paper_2502_13176_amd import synth
+        heads = 8
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        q64 = synth.storage_to_f64(q[0, :heads].view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        G = Hq // Hkv
+        n_kv = (heads + G - 1) // G
+        k64 = synth.storage_to_f64(k[0, :n_kv].view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        v64 = synth.storage_to_f64(v[0, :n_kv].view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        t0 = time.perf_counter()
+        want = [O.head_similarity(q64[h], k64[h // G], v64[h // G])[0] for h in range(heads)]
+        dt = time.perf_counter() - t0
+        got = sim[0, :heads].cpu().numpy()
+        row["cpu_baseline"] = {"value": round(heads * 2 * D * T * (T + 1) / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": int(threads), "kind": "oracle",
+                               "sample": f"fp64 oracle head_similarity on {heads} of {Hq} heads ({dt:.1f} s)"}
+        row["max_abs_error_vs_oracle_on_sample"] = float(np.max(np.abs(got - np.array(want))))
+    return row
 
 
 def read_traffic(workload, mode):
@@ -267,6 +334,9 @@ def main():
             "note": "every cache at capacity, fresh U(0,1) scores: nearly every kept row moves",
         }
     result["stream_probe"] = stream_probe(torch, B, arena.device)
+    if not args.no_profiling_row:
+        # the next row of the path after the decode loop's own: the one-time profiling kernel
+        result["profiling_kernel"] = profiling_row(torch, B, arena.device, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
     arena.close()

@@ -11,7 +11,7 @@
 // A workgroup of 4 wavefronts owns 128 consecutive tokens of one head, 32 per wavefront (two
 // 16-token column tiles that share every A operand read from LDS).  Keys and values arrive in
 // tiles of 64 rows, loaded by the whole workgroup and double-buffered in LDS; a wavefront skips
-// the 32-key slabs that lie entirely above its tokens (causal mask) and masks the others
+// the key tiles that lie entirely above its tokens (causal mask) and masks the others
 // element-wise.  The softmax normaliser cancels in the cosine, so the output is never divided.
 #include "common.h"
 
@@ -33,6 +33,7 @@ constexpr int kKeyTile = 64;                       // rows per LDS stage
 constexpr int kKStride = 272;                      // as in the decode kernel: conflict-free operand reads
 constexpr int kVStride = 288;
 constexpr float kNegInf = -__builtin_huge_valf();
+constexpr float kMaxSlack = 8.f;                   // a logit may exceed its token's reference maximum by this much
 constexpr float kCosEps = 1e-8f;                   // lower clamp of the product of the two norms
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256, 2) void profile_attn_kernel(ProfileParams p) {
   for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
     for (int bb = 0; bb < 8; ++bb) o[nt][bb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {kNegInf, kNegInf};
+  float m_ref[2] = {kNegInf, kNegInf};  // reference maximum of the exponent, log2 units
   float l_part[2] = {0.f, 0.f};
   const float cs = p.scale_log2e;
 
@@ -123,86 +124,115 @@ __global__ __launch_bounds__(256, 2) void profile_attn_kernel(ProfileParams p) {
     const bool more = kt + 1 < n_key_tiles;
     if (more) load_tile(kt + 1);
 
+    const int kt0 = kt * kKeyTile;        // first key of the tile
+    if (kt0 <= qw0 + kTokPerWave - 1) {   // else wholly above this wavefront's tokens (uniform per wavefront)
+      // ---- S^T = K Q^T for the tile's two 32-key slabs and both column tiles; every K operand is
+      //      read once.  A slab that is wholly masked for this wavefront (diagonal tile only) is
+      //      computed and masked like any other.
+      floatx4_t s[2][2][2];  // [slab][column tile][16-key tile]
+      // The 16 K operands of the tile (slab, 16-key tile, 32-element chunk) are read four ahead of
+      // their use, so that the matrix instructions do not wait for LDS.
+      const unsigned char* kbase = &lds_k[buf][n16 * kKStride + jg * 16];
+      u32x4_t ka[4];
 #pragma unroll
-    for (int slab = 0; slab < 2; ++slab) {
-      const int k0 = kt * kKeyTile + slab * 32;  // first key of the slab
-      if (k0 > qw0 + kTokPerWave - 1) continue;  // wholly above this wavefront's tokens (uniform per wavefront)
-      const unsigned char* ks = &lds_k[buf][slab * 32 * kKStride];
-      const unsigned char* vs = &lds_v[buf][slab * 32 * kVStride];
-
-      // ---- S^T = K Q^T for both column tiles; every K operand is read once ----------------------
-      floatx4_t s[2][2];
+      for (int i = 0; i < 4; ++i)
+        ka[i] = *reinterpret_cast<const u32x4_t*>(kbase + (i / 4) * 16 * kKStride + (i % 4) * 64);
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) s[nt][tt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const bf16x8_t a =
-              as_bf16x8(*reinterpret_cast<const u32x4_t*>(ks + (tt * 16 + n16) * kKStride + c * 64 + jg * 16));
-          s[0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[0][c], s[0][tt], 0, 0, 0);
-          s[1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[1][c], s[1][tt], 0, 0, 0);
+      for (int i = 0; i < 16; ++i) {
+        const int sl = i / 8, tt = (i / 4) % 2, c = i % 4;
+        if (c == 0) {
+          s[sl][0][tt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+          s[sl][1][tt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
         }
+        const bf16x8_t a = as_bf16x8(ka[i % 4]);
+        s[sl][0][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[0][c], s[sl][0][tt], 0, 0, 0);
+        s[sl][1][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qb[1][c], s[sl][1][tt], 0, 0, 0);
+        if (i + 4 < 16)
+          ka[i % 4] = *reinterpret_cast<const u32x4_t*>(kbase + ((i + 4) / 4) * 16 * kKStride + ((i + 4) % 4) * 64);
+      }
 
-      // ---- causal online softmax on the accumulator layout (lane (token, j): keys 4j..4j+3 of each
-      //      16-key tile); the weights become the B operand of the second product as they are ----
-      // each weight is split into a truncated bf16 high part and a bf16 residual, so the second
-      // product keeps ~16 bits of it (one bf16 term alone costs about 1e-3 on a token's cosine)
-      u32x4_t ph[2];
-      bf16x8_t pl[2];
-      const bool diag = k0 + 31 > qw0;  // some (key, token) pair of the slab is masked
+      // ---- causal mask (lane (token, j): keys 4j..4j+3 of each 16-key tile), raw maxima ----------
+      if (kt0 + kKeyTile - 1 > qw0) {  // some (key, token) pair of the tile is masked
+        // (the empty statement keeps this a real, wavefront-uniform branch: turned into selects it
+        // would run, and cost a quarter of the vector instructions, on every tile below the diagonal)
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (kt0 + sl * 32 + tt * 16 + jg * 4 + i > tok[nt]) s[sl][nt][tt][i] = kNegInf;
+      }
+      float mx[2];
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) {
-        float x[8];
+        mx[nt] = kNegInf;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) x[tt * 4 + i] = s[nt][tt][i] * cs;
-        if (diag) {
+        for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (k0 + tt * 16 + jg * 4 + i > tok[nt]) x[tt * 4 + i] = kNegInf;
-        }
-        float mx = x[0];
+            for (int i = 0; i < 4; ++i) mx[nt] = fmaxf(mx[nt], s[sl][nt][tt][i]);
+        mx[nt] *= cs;
+      }
+      // Lazy running maximum: the reference m_ref of a token only moves when a logit exceeds it by
+      // more than kMaxSlack (log2 units), so weights stay below 2^kMaxSlack and the rescale of the
+      // accumulators is rare after the first tile.  (First tile: m_ref = -inf, always taken; key 0
+      // is visible to every token, so the new reference is finite.)
+      if (__any(mx[0] > m_ref[0] + kMaxSlack) || __any(mx[1] > m_ref[1] + kMaxSlack)) {
 #pragma unroll
-        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, x[e]);
-        if (__any(mx > m_run[nt])) {
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float mn = fmaxf(m_run[nt], mx);  // finite: key 0 is visible to every token and comes first
-          const float alpha = fast_exp2(m_run[nt] - mn);
-          m_run[nt] = mn;
+        for (int nt = 0; nt < 2; ++nt) {
+          float m = mx[nt];
+          m = fmaxf(m, __shfl_xor(m, 16));
+          m = fmaxf(m, __shfl_xor(m, 32));
+          const float mn = fmaxf(m_ref[nt], m);
+          const float alpha = fast_exp2(m_ref[nt] - mn);
+          m_ref[nt] = mn;
           l_part[nt] *= alpha;
 #pragma unroll
           for (int bb = 0; bb < 8; ++bb) o[nt][bb] *= alpha;
         }
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const float p0 = fast_exp2(x[e] - m_run[nt]), p1 = fast_exp2(x[e + 1] - m_run[nt]);
-          l_part[nt] += p0 + p1;
-          const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
-          ph[nt][e / 2] = (u0 >> 16) | (u1 & 0xffff0000u);
-          pl[nt][e] = (__bf16)(p0 - __uint_as_float(u0 & 0xffff0000u));
-          pl[nt][e + 1] = (__bf16)(p1 - __uint_as_float(u1 & 0xffff0000u));
-        }
       }
 
-      // ---- O^T += V^T P^T; every transposed V operand is read once for both column tiles --------
-      const unsigned char* tr0 = vs + (jg * 4 + (n16 >> 2)) * kVStride + (n16 & 3) * 8;
+      // ---- weights and O^T += V^T P^T, slab by slab, in one basic block so that the vector work
+      //      of one slab can be scheduled between the matrix instructions of the other -----------
+      const float nm0 = -m_ref[0], nm1 = -m_ref[1];
 #pragma unroll
-      for (int bb = 0; bb < 8; ++bb) {
-        typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + bb * 32));
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + 16 * kVStride + bb * 32));
-        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[0]), o[0][bb], 0, 0, 0);
-        o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[1]), o[1][bb], 0, 0, 0);
-        o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[0], o[0][bb], 0, 0, 0);
-        o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[1], o[1][bb], 0, 0, 0);
+      for (int sl = 0; sl < 2; ++sl) {
+        // each weight is split into a truncated bf16 high part and a bf16 residual, so the second
+        // product keeps ~16 bits of it (one bf16 term alone costs about 1e-3 on a token's cosine)
+        u32x4_t ph[2];
+        bf16x8_t pl[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const float nm = nt ? nm1 : nm0;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const float p0 = fast_exp2(fmaf(s[sl][nt][e / 4][e % 4], cs, nm));
+            const float p1 = fast_exp2(fmaf(s[sl][nt][e / 4][e % 4 + 1], cs, nm));
+            l_part[nt] += p0 + p1;
+            const uint32_t u0 = __float_as_uint(p0), u1 = __float_as_uint(p1);
+            ph[nt][e / 2] = (u0 >> 16) | (u1 & 0xffff0000u);
+            pl[nt][e] = (__bf16)(p0 - __uint_as_float(u0 & 0xffff0000u));
+            pl[nt][e + 1] = (__bf16)(p1 - __uint_as_float(u1 & 0xffff0000u));
+          }
+        }
+        // every transposed V operand is read once for both column tiles
+        const unsigned char* tr0 = &lds_v[buf][(sl * 32 + jg * 4 + (n16 >> 2)) * kVStride + (n16 & 3) * 8];
+#pragma unroll
+        for (int bb = 0; bb < 8; ++bb) {
+          typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + bb * 32));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + 16 * kVStride + bb * 32));
+          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[0]), o[0][bb], 0, 0, 0);
+          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[1]), o[1][bb], 0, 0, 0);
+          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[0], o[0][bb], 0, 0, 0);
+          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[1], o[1][bb], 0, 0, 0);
+        }
       }
     }
 

@@ -142,3 +142,33 @@ def test_results_are_deterministic_and_errors_are_reported():
     st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, 4, 3, T, 128, B.BF16, None,
                                             sim.data_ptr(), ws.data_ptr(), 256, None)
     assert st == B.EINVAL
+
+
+def test_full_size_layer_sampled_heads_and_any_size_properties():
+    """The configuration bench.py times (one LLaMA-3-8B-shaped layer, prompt of 8192 tokens): three
+    heads against the oracle token by token, every head against properties that hold at any size."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    Hq, Hkv, T, D = 32, 8, 8192, 128
+    q = torch.randn((1, Hq, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((1, Hkv, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((1, Hkv, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sim, cos = B.profile_similarity(q, k, v)
+    torch.cuda.synchronize()
+    sim_h, cos_h = sim.cpu().numpy().astype(np.float64), cos.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(cos_h)) and np.all(np.abs(cos_h) <= 1.0 + 1e-5)
+    assert np.all(np.abs(cos_h[0, :, 0] - 1.0) <= 1e-6)                 # every head's first token
+    assert np.allclose(sim_h[0], cos_h[0].mean(axis=1), rtol=0, atol=1e-5)
+    H = _h()
+    G = Hq // Hkv
+    worst = 0.0
+    for h in (0, 13, 31):
+        q64 = synth.storage_to_f64(H.from_device_storage(q[0, h], "bf16"), "bf16")
+        k64 = synth.storage_to_f64(H.from_device_storage(k[0, h // G], "bf16"), "bf16")
+        v64 = synth.storage_to_f64(H.from_device_storage(v[0, h // G], "bf16"), "bf16")
+        want_mean, want_cos = O.head_similarity(q64, k64, v64)
+        e = float(np.max(np.abs(cos_h[0, h] - want_cos)))
+        assert e <= COS_TOL and abs(sim_h[0, h] - want_mean) <= MEAN_TOL
+        worst = max(worst, e)
+    print(f"T=8192 layer: worst per-token cosine error on 3 sampled heads {worst:.2e}", flush=True)

@@ -21,6 +21,9 @@ Pins (see tests/test_oracle_*.py):
                          tokens, uniform attention = prefix means, identity
                          attention), scale invariance, torch fp64 causal SDPA
   kv_importance          hand-computed values, range and monotonicity
+  prefill_scores         pure-Python brute force, total mass G*T, harmonic closed
+                         form for uniform attention, torch fp64 softmax of the
+                         masked logits, consistency with decode_attn's weights
 """
 from __future__ import annotations
 
@@ -339,4 +342,34 @@ def kv_importance(similarity: np.ndarray, G: int) -> np.ndarray:
         raise ValueError("Hq must be a multiple of G")
     grouped = s.reshape(L, Hq // G, G).mean(axis=2)
     return 1.0 - (grouped + 1.0) / 2.0
+
+
+# ---------------------------------------------------------------------------
+# Scores of a whole prompt at once (the eviction that precedes the decode loop)
+# ---------------------------------------------------------------------------
+
+def prefill_scores(Q: np.ndarray, K: np.ndarray) -> np.ndarray:
+    """Accumulated attention of every prompt token after a prefill of T tokens.
+
+    Q: [G, T, D] query rows of the G heads that share the cache, K: [T, D].
+    score_j = sum_g sum_{t >= j} p_g[t, j] with p_g[t, :] = softmax over j <= t of
+    q_g[t] . k_j / sqrt(D): the column sums of the causal attention matrices, i.e.
+    exactly what score_accumulate would have built up had the T tokens been
+    decoded one by one without eviction (the heavy-hitter statistic the paper
+    cites as a compatible eviction policy, applied to f_evict of Eqs. 5-6 before
+    the first decode step).  Returns [T] fp64.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    G, T, D = Q.shape
+    if K.shape != (T, D) or T < 1:
+        raise ValueError("Q must be [G, T, D] and K [T, D] with T >= 1")
+    score = np.zeros(T, dtype=np.float64)
+    scale = 1.0 / math.sqrt(D)
+    for g in range(G):
+        for t in range(T):
+            s = (K[: t + 1] @ Q[g, t]) * scale
+            w = np.exp(s - s.max())
+            score[: t + 1] += w / w.sum()
+    return score
 

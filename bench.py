@@ -128,7 +128,7 @@ def profiling_row(torch, B, device, with_cpu_baseline, T=8192, Hq=32, Hkv=8, rep
 
     def run():
         st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, Hq, Hkv, T, D, B.BF16,
-                                                None, sim.data_ptr(), ws.data_ptr(), nbytes, stream)
+                                                None, sim.data_ptr(), None, ws.data_ptr(), nbytes, stream)
         if st != B.OK:
             raise RuntimeError(f"baklava_profile_similarity: status {st}")
     run()

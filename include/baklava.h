@@ -272,7 +272,8 @@ int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode
  * q DEVICE bf16 [batch, Hq, T, D]; k, v DEVICE bf16 [batch, Hkv, T, D] (query head h reads KV head
  * h / (Hq/Hkv)); all 16-byte aligned.  D must be 128 and dtype BAKLAVA_BF16.
  * cos_out DEVICE fp32 [batch, Hq, T] (per-token cosines) or NULL; sim_out DEVICE fp32 [batch, Hq]
- * (mean per head).  A cosine whose norm product is below 1e-8 is divided by 1e-8 instead (a zero
+ * (mean per head); lse_out DEVICE fp32 [batch, Hq, T] or NULL: per token, log2 of the sum over its
+ * visible keys of 2^(q_t.k_j log2(e)/sqrt(D)), the softmax normaliser baklava_prefill_scores needs.  A cosine whose norm product is below 1e-8 is divided by 1e-8 instead (a zero
  * row gives 0).  workspace DEVICE, at least baklava_profile_workspace_bytes(batch, Hq, T) bytes,
  * 16-byte aligned, owned by the caller and free again once the stream has passed the call.
  * Enqueues two kernels on `stream`, does not synchronise.  Results are deterministic.
@@ -281,7 +282,27 @@ int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode
 size_t baklava_profile_workspace_bytes(int32_t batch, int32_t Hq, int32_t T);
 int baklava_profile_similarity(const void* q, const void* k, const void* v, int32_t batch, int32_t Hq,
                                int32_t Hkv, int32_t T, int32_t D, int32_t dtype, float* cos_out,
-                               float* sim_out, void* workspace, size_t workspace_bytes, void* stream);
+                               float* sim_out, float* lse_out, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/*
+ * Attention scores of a whole prompt at once, for the eviction that precedes the decode loop
+ * (f_evict of Eqs. 5-6 applied to a prefilled cache with the accumulated-attention policy):
+ * score_j = sum over the Hq/Hkv query heads of the KV head and over the prompt tokens t >= j of the
+ * causal softmax weight of key j for token t, i.e. what baklava_decode_attn's score tracking would
+ * have accumulated had the T tokens been decoded one by one without eviction.
+ * q DEVICE bf16 [batch, Hq, T, D]; lse DEVICE fp32 [batch, Hq, T] as written by
+ * baklava_profile_similarity (or by any attention pass: log2-sum-exp of the scaled logits in log2
+ * units); k DEVICE bf16: the T rows of sequence (b, KV head h) start at row row_off[b*Hkv + h] of the
+ * plane (row_off DEVICE int64, e.g. a slice of an arena's offset table with k its K plane), or at
+ * row (b*Hkv + h)*T when row_off is NULL; score_out DEVICE fp32, addressed by rows like k (e.g. the
+ * arena's score plane): the T scores of every sequence are overwritten.  D must be 128, dtype
+ * BAKLAVA_BF16.  Enqueues one kernel on `stream`; deterministic.
+ * Errors: EINVAL (null, misaligned, bad shape), EHIP.
+ */
+int baklava_prefill_scores(const void* q, const void* k, const float* lse, const int64_t* row_off,
+                           int32_t batch, int32_t Hq, int32_t Hkv, int32_t T, int32_t D, int32_t dtype,
+                           float* score_out, void* stream);
 
 /*
  * Algorithm 1, step 2, with the normalisation of "Head Importance Heuristic" (host only): the

@@ -29,7 +29,7 @@ EXPORTS = [
     "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
-    "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance",
+    "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance", "baklava_prefill_scores",
 ]
 
 
@@ -95,7 +95,9 @@ def lib() -> C.CDLL:
     L.baklava_profile_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     L.baklava_profile_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
-                                             C.c_size_t, C.c_void_p]
+                                             C.c_void_p, C.c_size_t, C.c_void_p]
+    L.baklava_prefill_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                         C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.baklava_kv_importance.argtypes = [f64p, C.c_int32, C.c_int32, C.c_int32, f64p]
     for name in EXPORTS:
         if name not in ("baklava_strerror", "baklava_workspace_bytes", "baklava_profile_workspace_bytes"):
@@ -301,9 +303,10 @@ def profile_workspace_bytes(batch: int, Hq: int, T: int) -> int:
     return int(lib().baklava_profile_workspace_bytes(batch, Hq, T))
 
 
-def profile_similarity(q, k, v, want_cos: bool = True, stream=None):
+def profile_similarity(q, k, v, want_cos: bool = True, want_lse: bool = False, stream=None):
     """baklava_profile_similarity on torch device tensors q [batch, Hq, T, D], k / v [batch, Hkv, T, D]
-    (bf16).  Returns (sim [batch, Hq], cos [batch, Hq, T] or None) as torch fp32 device tensors."""
+    (bf16).  Returns (sim [batch, Hq], cos [batch, Hq, T] or None) as torch fp32 device tensors, and
+    the per-token log2-sum-exp [batch, Hq, T] as a third value when want_lse is set."""
     import torch
     batch, Hq, T, D = q.shape
     Hkv = k.shape[1]
@@ -315,10 +318,20 @@ def profile_similarity(q, k, v, want_cos: bool = True, stream=None):
         raise ValueError("contiguous tensors expected")
     sim = torch.empty((batch, Hq), dtype=torch.float32, device=q.device)
     cos = torch.empty((batch, Hq, T), dtype=torch.float32, device=q.device) if want_cos else None
+    lse = torch.empty((batch, Hq, T), dtype=torch.float32, device=q.device) if want_lse else None
     nbytes = profile_workspace_bytes(batch, Hq, T)
     ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=q.device)
     _check(lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), batch, Hq, Hkv, T, D, BF16,
-                                            cos.data_ptr() if want_cos else None, sim.data_ptr(), ws.data_ptr(),
+                                            cos.data_ptr() if want_cos else None, sim.data_ptr(),
+                                            lse.data_ptr() if want_lse else None, ws.data_ptr(),
                                             nbytes, _stream_ptr(stream)), "baklava_profile_similarity")
-    return sim, cos
+    return (sim, cos, lse) if want_lse else (sim, cos)
+
+
+def prefill_scores(q, k_plane, lse, score_plane, batch: int, Hq: int, Hkv: int, T: int, row_off=None, stream=None):
+    """baklava_prefill_scores: q [batch, Hq, T, 128] bf16, lse [batch, Hq, T] fp32, k_plane a bf16 tensor of
+    rows of 128 elements, score_plane fp32 rows, row_off an int64 device tensor [batch * Hkv] or None (dense)."""
+    _check(lib().baklava_prefill_scores(q.data_ptr(), k_plane.data_ptr(), lse.data_ptr(),
+                                        row_off.data_ptr() if row_off is not None else None, batch, Hq, Hkv, T, 128,
+                                        BF16, score_plane.data_ptr(), _stream_ptr(stream)), "baklava_prefill_scores")
 

@@ -539,17 +539,31 @@ extern "C" size_t baklava_profile_workspace_bytes(int32_t batch, int32_t Hq, int
 
 extern "C" int baklava_profile_similarity(const void* q, const void* k, const void* v, int32_t batch,
                                           int32_t Hq, int32_t Hkv, int32_t T, int32_t D, int32_t dtype,
-                                          float* cos_out, float* sim_out, void* workspace,
+                                          float* cos_out, float* sim_out, float* lse_out, void* workspace,
                                           size_t workspace_bytes, void* stream) {
   if (!q || !k || !v || !sim_out || !workspace) return BAKLAVA_EINVAL;
   if (batch <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || Hq % Hkv) return BAKLAVA_EINVAL;
   if (D != 128 || dtype != BAKLAVA_BF16) return BAKLAVA_EINVAL;
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)workspace) & 15) return BAKLAVA_EINVAL;
-  if (((uintptr_t)sim_out | (uintptr_t)cos_out) & 3) return BAKLAVA_EINVAL;
+  if (((uintptr_t)sim_out | (uintptr_t)cos_out | (uintptr_t)lse_out) & 3) return BAKLAVA_EINVAL;
   if ((int64_t)batch * Hq * (((int64_t)T + 127) / 128) > INT32_MAX) return BAKLAVA_EINVAL;
   if (workspace_bytes < baklava_profile_workspace_bytes(batch, Hq, T)) return BAKLAVA_ECAPACITY;
-  if (!hip_ok(launch_profile_similarity(q, k, v, batch, Hq, Hkv, T, cos_out, sim_out,
+  if (!hip_ok(launch_profile_similarity(q, k, v, batch, Hq, Hkv, T, cos_out, sim_out, lse_out,
                                         reinterpret_cast<float*>(workspace), (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
+extern "C" int baklava_prefill_scores(const void* q, const void* k, const float* lse, const int64_t* row_off,
+                                      int32_t batch, int32_t Hq, int32_t Hkv, int32_t T, int32_t D,
+                                      int32_t dtype, float* score_out, void* stream) {
+  if (!q || !k || !lse || !score_out) return BAKLAVA_EINVAL;
+  if (batch <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || Hq % Hkv) return BAKLAVA_EINVAL;
+  if (D != 128 || dtype != BAKLAVA_BF16) return BAKLAVA_EINVAL;
+  if (((uintptr_t)q | (uintptr_t)k) & 15) return BAKLAVA_EINVAL;
+  if (((uintptr_t)lse | (uintptr_t)score_out) & 3 || ((uintptr_t)row_off & 7)) return BAKLAVA_EINVAL;
+  if ((int64_t)batch * Hkv * (((int64_t)T + 127) / 128) > INT32_MAX) return BAKLAVA_EINVAL;
+  if (!hip_ok(launch_prefill_scores(q, k, lse, row_off, batch, Hq, Hkv, T, score_out, (hipStream_t)stream)))
     return BAKLAVA_EHIP;
   return BAKLAVA_OK;
 }

@@ -124,7 +124,10 @@ struct CompactParams {
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s);
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
-                                     int T, float* cos_out, float* sim_out, float* tile_sum, hipStream_t s);
+                                     int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
+                                     hipStream_t s);
+hipError_t launch_prefill_scores(const void* q, const void* k, const float* lse, const int64_t* row_off,
+                                 int batch, int Hq, int Hkv, int T, float* score, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s);
 // max_count: the largest row count of a work item in the launched range (or a bound on it)
 hipError_t launch_score_update(const DecodeParams& p, int n_items, int max_count, hipStream_t s);

@@ -44,6 +44,7 @@ struct ProfileParams {
   const unsigned char* k;  // [batch, Hkv, T, D]
   const unsigned char* v;
   float* cos_out;          // [batch, Hq, T] or null
+  float* lse_out;          // [batch, Hq, T] or null: log2 of the sum over visible keys of 2^(scaled logit)
   float* tile_sum;         // [batch * Hq, n_tiles] sum of the cosines of each 128-token tile
   int32_t T, Hq, Hkv, n_tiles;
   float scale_log2e;
@@ -268,6 +269,7 @@ __global__ __launch_bounds__(256, 2) void profile_attn_kernel(ProfileParams p) {
     const bool live = tok[nt] < T && jg == 0;
     if (live) {
       if (p.cos_out) p.cos_out[(int64_t)bh * T + tok[nt]] = cosv;
+      if (p.lse_out) p.lse_out[(int64_t)bh * T + tok[nt]] = m_ref[nt] + __builtin_log2f(l_tot);
       wsum += cosv;
     }
   }
@@ -293,12 +295,14 @@ __global__ __launch_bounds__(64) void profile_mean_kernel(const float* tile_sum,
 }  // namespace
 
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
-                                     int T, float* cos_out, float* sim_out, float* tile_sum, hipStream_t s) {
+                                     int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
+                                     hipStream_t s) {
   ProfileParams p;
   p.q = reinterpret_cast<const unsigned char*>(q);
   p.k = reinterpret_cast<const unsigned char*>(k);
   p.v = reinterpret_cast<const unsigned char*>(v);
   p.cos_out = cos_out;
+  p.lse_out = lse_out;
   p.tile_sum = tile_sum;
   p.T = T; p.Hq = Hq; p.Hkv = Hkv;
   p.n_tiles = (T + kTokPerWg - 1) / kTokPerWg;

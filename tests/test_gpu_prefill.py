@@ -1,0 +1,126 @@
+"""GPU parity: baklava_prefill_scores (column sums of the causal attention matrices) against the
+oracle, and the prefill -> scores -> eviction path end to end on a ragged arena."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import baklava_oracle as O
+from paper_2502_13176_amd import binding as B
+from paper_2502_13176_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+# A score is a sum of up to G*T softmax weights, each 2^(fp32 logit - fp32 log-sum-exp): relative
+# error per weight ~ (|logit| + |lse|) * 2^-24 * ln 2 plus the hardware exp2/log2 approximations
+# (~1e-6), accumulated in fp32.  Bound taken: 2e-5 relative to max(1, score) (measured ~2e-6).
+SCORE_RTOL = 2e-5
+LSE_TOL = 1e-4  # log2 units, against the oracle's fp64 log-sum-exp
+
+
+def _h():
+    import gpu_harness
+    return gpu_harness
+
+
+def oracle_lse2(q64, k64):
+    """fp64 log2-sum-exp of the scaled causal logits, written out from its definition."""
+    T, D = q64.shape
+    out = np.empty(T)
+    for t in range(T):
+        s = (k64[: t + 1] @ q64[t]) / np.sqrt(D) * np.log2(np.e)
+        m = s.max()
+        out[t] = m + np.log2(np.sum(np.exp2(s - m)))
+    return out
+
+
+def run_dense(batch, Hq, Hkv, T, seed, peaked=False, qscale=1.0):
+    H = _h()
+    dev = torch.device("cuda:0")
+    rng = np.random.Generator(np.random.PCG64(seed))
+    qb = synth.f32_to_bf16_bits(qscale * rng.standard_normal((batch, Hq, T, 128), dtype=np.float32))
+    kb = synth.payload(rng, (batch, Hkv, T, 128), "bf16", peaked=peaked)
+    vb = synth.payload(rng, (batch, Hkv, T, 128), "bf16")
+    q, k, v = (H.to_device_storage(x, "bf16", dev) for x in (qb, kb, vb))
+    _, _, lse = B.profile_similarity(q, k, v, want_cos=False, want_lse=True)
+    score = torch.full((batch * Hkv * T,), float("nan"), dtype=torch.float32, device=dev)
+    B.prefill_scores(q, k, lse, score, batch, Hq, Hkv, T)
+    torch.cuda.synchronize()
+    got = score.cpu().numpy().astype(np.float64).reshape(batch, Hkv, T)
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    q64, k64 = synth.storage_to_f64(qb, "bf16"), synth.storage_to_f64(kb, "bf16")
+    G = Hq // Hkv
+    worst = 0.0
+    for b in range(batch):
+        for h in range(Hkv):
+            want = O.prefill_scores(q64[b, h * G:(h + 1) * G], k64[b, h])
+            err = np.abs(got[b, h] - want) / np.maximum(1.0, want)
+            assert np.all(np.isfinite(got[b, h]))
+            assert err.max() <= SCORE_RTOL, f"batch {b} kv head {h}: relative score error {err.max():.3e}"
+            assert abs(got[b, h].sum() - G * T) <= 1e-4 * G * T          # every attention row sums to 1
+            worst = max(worst, float(err.max()))
+        for hq in range(0, Hq, max(1, Hq // 3)):
+            want_lse = oracle_lse2(q64[b, hq], k64[b, hq // G])
+            assert np.max(np.abs(lse_h[b, hq] - want_lse)) <= LSE_TOL
+    return worst
+
+
+@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 200, 257, 400])
+def test_prompt_lengths_around_every_tile_boundary(T):
+    worst = run_dense(1, 4, 2, T, 9600 + T)
+    print(f"T={T}: worst relative score error {worst:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("batch,Hq,Hkv", [(2, 8, 2), (1, 7, 1), (3, 2, 2), (1, 16, 1)])
+def test_head_grouping_and_batches(batch, Hq, Hkv):
+    run_dense(batch, Hq, Hkv, 300, 9700 + Hq)
+
+
+def test_peaked_and_large_logits():
+    run_dense(1, 4, 2, 350, 9800, peaked=True, qscale=4.0)
+
+
+def test_prefill_then_eviction_on_a_ragged_arena():
+    """A prompt of T tokens is written into every cache of a layer (capacity >= T), the scores come
+    from the kernel, and one eviction brings every cache down to its own budget: kept lists bit-exact
+    against the oracle's selection on the kernel's scores, scores within tolerance of the oracle's."""
+    H = _h()
+    T = 1500
+    w = synth.shrink(synth.WORKLOADS["llama32"], name="prefill", L=2, Hq=8, Hkv=4, batch=2, seed=31, sink=4,
+                     recent=32, slack=T)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = [100, 450, 37, 1499, 800, 64, 300, 1200]             # per (layer, KV head)
+    arena = H.make_arena(w, budgets)
+    lens = [T] * arena.n_caches
+    st = H.fill_from_host(arena, w, lens, rng, scores="zero")
+    dev = arena.device
+    cpl = w.batch * w.Hkv
+    G = w.G
+    for layer in range(w.L):
+        qb = synth.payload(rng, (w.batch, w.Hq, T, w.D), "bf16")
+        q = H.to_device_storage(qb, "bf16", dev)
+        q64 = synth.storage_to_f64(qb, "bf16")
+        # dense copies of the layer's K / V rows for the attention pass that yields the normalisers
+        kd = torch.stack([arena.k[int(arena.off_host[layer * cpl + s]):int(arena.off_host[layer * cpl + s]) + T]
+                          for s in range(cpl)]).view(w.batch, w.Hkv, T, w.D).contiguous()
+        vd = torch.stack([arena.v[int(arena.off_host[layer * cpl + s]):int(arena.off_host[layer * cpl + s]) + T]
+                          for s in range(cpl)]).view(w.batch, w.Hkv, T, w.D).contiguous()
+        _, _, lse = B.profile_similarity(q, kd, vd, want_cos=False, want_lse=True)
+        # scores straight into the arena's score plane, K read from the arena through its offset table
+        B.prefill_scores(q, arena.k, lse, arena.score, w.batch, w.Hq, w.Hkv, T, row_off=arena.off[layer * cpl:(layer + 1) * cpl])
+        torch.cuda.synchronize()
+        for s in range(cpl):
+            c = layer * cpl + s
+            b, h = divmod(s, w.Hkv)
+            o = int(arena.off_host[c])
+            got = arena.score[o:o + T].cpu().numpy()
+            want = O.prefill_scores(q64[b, h * G:(h + 1) * G], synth.storage_to_f64(st.K[c], "bf16"))
+            assert np.max(np.abs(got - want) / np.maximum(1.0, want)) <= SCORE_RTOL
+            st.score[c] = got                                       # selection is judged on the kernel's own fp32 scores
+    from test_gpu_compact import run_compact_and_check
+    after = run_compact_and_check(arena, w, st)
+    assert arena.lengths().tolist() == [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]
+    # the sink rows and the recent window survive in every cache
+    for c in range(arena.n_caches):
+        pos = after.pos[c].tolist()
+        assert pos[:4] == [0, 1, 2, 3] and pos[-32:] == list(range(T - 32, T))
+    arena.close()

@@ -134,13 +134,13 @@ def test_results_are_deterministic_and_errors_are_reported():
     sim = torch.empty((1, 4), dtype=torch.float32, device=dev)
     ws = torch.empty((256,), dtype=torch.uint8, device=dev)
     st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, 4, 2, T, 128, B.BF16, None,
-                                            sim.data_ptr(), ws.data_ptr(), 8, None)
+                                            sim.data_ptr(), None, ws.data_ptr(), 8, None)
     assert st == B.ECAPACITY
     st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, 4, 2, T, 64, B.BF16, None,
-                                            sim.data_ptr(), ws.data_ptr(), 256, None)
+                                            sim.data_ptr(), None, ws.data_ptr(), 256, None)
     assert st == B.EINVAL
     st = B.lib().baklava_profile_similarity(q.data_ptr(), k.data_ptr(), v.data_ptr(), 1, 4, 3, T, 128, B.BF16, None,
-                                            sim.data_ptr(), ws.data_ptr(), 256, None)
+                                            sim.data_ptr(), None, ws.data_ptr(), 256, None)
     assert st == B.EINVAL
 
 

@@ -34,7 +34,7 @@ def parse_args():
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
     ap.add_argument("--no-profiling-row", action="store_true",
-                    help="skip the measurement of the one-time profiling kernel")
+                    help="skip the measurements of the one-time profiling kernel and of the prompt-wide scores")
     ap.add_argument("--target-items-whole", type=int, default=-1,
                     help="work items per whole-model launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--target-items", type=int, default=-1,
@@ -173,6 +173,79 @@ def profiling_row(torch, B, device, with_cpu_baseline, T=8192, Hq=32, Hkv=8, rep
                                "cores": int(threads), "kind": "oracle",
                                "sample": f"fp64 oracle head_similarity on {heads} of {Hq} heads ({dt:.1f} s)"}
         row["max_abs_error_vs_oracle_on_sample"] = float(np.max(np.abs(got - np.array(want))))
+    return row
+
+
+def prefill_row(torch, B, synth, device, with_cpu_baseline, T=32768, reps=5):
+    """The step before the decode loop for one sequence of the llama32 workload: attention scores of
+    a T-token prompt for every cache of one layer (column sums of the causal attention matrices, first
+    product only: D T (T+1) algorithmic flops per head), then one eviction from T rows to the layer's
+    ragged budgets."""
+    import numpy as np
+    w = synth.WORKLOADS["llama32"]
+    Hq, Hkv, D = w.Hq, w.Hkv, w.D
+    budgets = synth.budgets_for(w, B.alloc_proportional)[:Hkv]          # layer 0 of the workload
+    arena = B.Arena(1, Hq, Hkv, D, 1, w.dtype, budgets, T, w.sink, w.recent)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(777)
+    q = torch.randn((1, Hq, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((1, Hkv, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((1, Hkv, T, D), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    for c in range(arena.n_caches):
+        o = int(arena.off_host[c])
+        arena.k[o:o + T].copy_(k[0, c])
+        arena.v[o:o + T].copy_(v[0, c])
+    arena.pos.zero_()
+    arena.set_lengths(np.full(arena.n_caches, T, dtype=np.int32))
+    _, _, lse = B.profile_similarity(q, k, v, want_cos=False, want_lse=True)
+
+    def run():
+        B.prefill_scores(q, arena.k, lse, arena.score, 1, Hq, Hkv, T, row_off=arena.off)
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = Hq * D * T * (T + 1)
+    e0.record()
+    arena.compact(0, 1)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_evict = e0.elapsed_time(e1)
+    kept = int(arena.lengths().astype(np.int64).sum())
+    row = {
+        "what": "attention scores of a whole prompt (column sums of the causal attention matrices) for one layer, "
+                "then one eviction from the prompt length to the layer's budgets",
+        "config": {"workload": f"one sequence of llama32, one layer: {Hq} heads, {Hkv} KV heads, D={D}, prompt of {T} "
+                               f"tokens, budgets {min(budgets)}..{max(budgets)} rows"},
+        "scores_us": round(ms * 1e3, 1),
+        "roofline": {"bound": "mfma", "kernel": "prefill_score_kernel", "achieved": round(flops / ms / 1e9, 1),
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / ms / 1e9 / 2500.0, 4), "traffic": None,
+                     "algorithmic_flops_per_launch": flops},
+        "eviction_us": round(ms_evict * 1e3, 1), "rows_before": Hkv * T, "rows_kept": kept,
+    }
+    if with_cpu_baseline:
+        import time
+        from oracle import baklava_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        Ts, G = 4096, Hq // Hkv
+        q64 = synth.storage_to_f64(q[0, :G, :Ts].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        k64 = synth.storage_to_f64(k[0, 0, :Ts].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        t0 = time.perf_counter()
+        O.prefill_scores(q64, k64)
+        dt = time.perf_counter() - t0
+        row["cpu_baseline"] = {"value": round(G * D * Ts * (Ts + 1) / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads),
+                               "kind": "oracle", "sample": f"fp64 oracle prefill_scores on the first {Ts} tokens of one "
+                                                            f"KV head's {G} query heads ({dt:.1f} s)"}
+    arena.close()
     return row
 
 
@@ -337,6 +410,7 @@ def main():
     if not args.no_profiling_row:
         # the next row of the path after the decode loop's own: the one-time profiling kernel
         result["profiling_kernel"] = profiling_row(torch, B, arena.device, not args.no_cpu_baseline)
+        result["prefill_scores"] = prefill_row(torch, B, synth, arena.device, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
     arena.close()

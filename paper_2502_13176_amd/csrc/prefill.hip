@@ -14,7 +14,8 @@
 // over the G query heads and, for each, over the tokens from its first key to the end of the
 // prompt in tiles of 64, double-buffered in LDS.  Column sums stay in registers (one partial per
 // lane and key) and are reduced over the 16 token lanes once, at the end: no atomics, results are
-// deterministic.  Workgroups with the most tokens (the first keys) are launched first.
+// deterministic.  Key block i streams T - 128 i tokens, so a workgroup takes blocks i and
+// n_blocks - 1 - i: equal work for every workgroup of a sequence.
 #include "common.h"
 
 namespace baklava {
@@ -54,15 +55,22 @@ __global__ __launch_bounds__(256) void prefill_score_kernel(PrefillParams p) {
   const int lane = tid & 63, wave = tid >> 6;
   const int n16 = lane & 15, jg = lane >> 4;
   const int T = p.T;
-  const int n_seq = gridDim.x / p.n_blocks;   // batch * Hkv
+  const int n_pairs = (p.n_blocks + 1) / 2;
+  const int n_seq = gridDim.x / n_pairs;      // batch * Hkv
   const int seq = blockIdx.x % n_seq;         // (b, kv head)
-  const int block = blockIdx.x / n_seq;       // key block, ascending: most tokens first
+  const int pair = blockIdx.x / n_seq;
   const int G = p.Hq / p.Hkv;
   const int b = seq / p.Hkv, hk = seq % p.Hkv;
   const int64_t row0 = p.row_off ? p.row_off[seq] : (int64_t)seq * T;
   const unsigned char* Kb = p.k + row0 * (kD * 2);
 
-  const int j0 = block * kKeysPerWg;          // first key of the workgroup
+  const float cs = p.scale_log2e;
+  // Key block i sees T - 128 i tokens: the workgroup takes blocks i and n_blocks - 1 - i, one after
+  // the other, so that every workgroup of a sequence streams (about) the same number of tokens.
+  for (int half = 0; half < 2; ++half) {
+  const int block = half == 0 ? pair : p.n_blocks - 1 - pair;
+  if (half == 1 && block == pair) break;      // odd number of blocks: the middle one is alone
+  const int j0 = block * kKeysPerWg;          // first key of the block
   const int jw0 = j0 + wave * kKeysPerWave;   // first key of this wavefront
 
   // A operand: lane (key % 16, j), 16-key tile tt, chunk c holds K[key][32c + 8j .. +8); loaded once.
@@ -78,7 +86,6 @@ __global__ __launch_bounds__(256) void prefill_score_kernel(PrefillParams p) {
   float acc[8];  // column-sum partials of keys jw0 + 16 tt + 4 jg + i (e = 4 tt + i), over this lane's tokens
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  const float cs = p.scale_log2e;
 
   // Stages: for each query head of the group, the token tiles from the one holding key j0 to the end.
   const int first_tile = j0 / kTokTile;
@@ -167,6 +174,7 @@ __global__ __launch_bounds__(256) void prefill_score_kernel(PrefillParams p) {
       if (key < T) p.score[row0 + key] = acc[e];
     }
   }
+  }
 }
 
 }  // namespace
@@ -182,7 +190,7 @@ hipError_t launch_prefill_scores(const void* q, const void* k, const float* lse,
   p.T = T; p.Hq = Hq; p.Hkv = Hkv;
   p.n_blocks = (T + kKeysPerWg - 1) / kKeysPerWg;
   p.scale_log2e = 1.4426950408889634f / sqrtf((float)kD);
-  const int64_t n_wg = (int64_t)batch * Hkv * p.n_blocks;
+  const int64_t n_wg = (int64_t)batch * Hkv * ((p.n_blocks + 1) / 2);
   if (n_wg <= 0 || n_wg > INT32_MAX) return hipErrorInvalidValue;
   prefill_score_kernel<<<dim3((unsigned)n_wg), dim3(256), 0, s>>>(p);
   return hipGetLastError();

@@ -124,3 +124,58 @@ def test_prefill_then_eviction_on_a_ragged_arena():
         pos = after.pos[c].tolist()
         assert pos[:4] == [0, 1, 2, 3] and pos[-32:] == list(range(T - 32, T))
     arena.close()
+
+
+def test_full_size_prompt_scores_and_large_ratio_eviction():
+    """One LLaMA-3-8B-shaped layer with a prompt of 32768 tokens per cache: the scores' total mass
+    and the last 128 columns of two caches against the oracle (those need only the last rows'
+    normalisers), then one eviction from 32768 rows to ragged budgets of 128..16384 rows with the
+    kept lists judged on the kernel's scores."""
+    H = _h()
+    T = 32768
+    w = synth.shrink(synth.WORKLOADS["llama32"], name="prefill32k", L=1, Hq=32, Hkv=8, batch=1, seed=32, sink=4,
+                     recent=64, slack=T)
+    budgets = [128, 16384, 4096, 700, 9999, 2048, 333, 12000]
+    arena = H.make_arena(w, budgets)
+    dev = arena.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    q = torch.randn((1, w.Hq, T, w.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    kd = torch.randn((1, w.Hkv, T, w.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vd = torch.randn((1, w.Hkv, T, w.D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    for c in range(arena.n_caches):
+        o = int(arena.off_host[c])
+        arena.k[o:o + T].copy_(kd[0, c])
+        arena.v[o:o + T].copy_(vd[0, c])
+        arena.pos[o:o + T].copy_(torch.arange(T, dtype=torch.int32, device=dev))
+    arena.set_lengths(np.full(arena.n_caches, T, dtype=np.int32))
+    _, _, lse = B.profile_similarity(q, kd, vd, want_cos=False, want_lse=True)
+    B.prefill_scores(q, arena.k, lse, arena.score, 1, w.Hq, w.Hkv, T, row_off=arena.off)
+    torch.cuda.synchronize()
+    G = w.G
+    tail = 128
+    for c in range(arena.n_caches):
+        o = int(arena.off_host[c])
+        got = arena.score[o:o + T].cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got)) and np.all(got >= 0)
+        assert abs(got.sum() - G * T) <= 1e-4 * G * T
+        assert 0 < got[-1] <= G + 1e-4
+        if c in (0, 5):
+            # columns j >= T - tail: only rows t >= j contribute, each needs its full softmax
+            q64 = synth.storage_to_f64(H.from_device_storage(q[0, c * G:(c + 1) * G, T - tail:], "bf16"), "bf16")
+            k64 = synth.storage_to_f64(H.from_device_storage(kd[0, c], "bf16"), "bf16")
+            want = np.zeros(tail)
+            for g in range(G):
+                for i in range(tail):
+                    t = T - tail + i
+                    s = (k64[: t + 1] @ q64[g, i]) / np.sqrt(w.D)
+                    p = np.exp(s - s.max())
+                    p /= p.sum()
+                    want[: i + 1] += p[T - tail: t + 1]
+            err = np.abs(got[-tail:] - want) / np.maximum(1.0, want)
+            assert err.max() <= SCORE_RTOL, f"cache {c}: {err.max():.3e}"
+    st = H.download(arena, w)
+    from test_gpu_compact import run_compact_and_check
+    run_compact_and_check(arena, w, st)
+    assert arena.lengths().tolist() == budgets
+    arena.close()

@@ -21,6 +21,12 @@ Pins (see tests/test_oracle_*.py):
                          tokens, uniform attention = prefix means, identity
                          attention), scale invariance, torch fp64 causal SDPA
   kv_importance          hand-computed values, range and monotonicity
+  layer_similarity       closed forms (identical, opposite, orthogonal rows), brute
+                         force, torch fp64 cosine_similarity, scale invariance
+  alloc_two_level        conservation per layer and overall, reduction to its two
+                         building blocks; the paper does not say how layer scores
+                         become layer budgets -> the composition is a reading,
+                         PARITY UNPINNED beyond those invariants
   prefill_scores         pure-Python brute force, total mass G*T, harmonic closed
                          form for uniform attention, torch fp64 softmax of the
                          masked logits, consistency with decode_attn's weights
@@ -372,4 +378,58 @@ def prefill_scores(Q: np.ndarray, K: np.ndarray) -> np.ndarray:
             w = np.exp(s - s.max())
             score[: t + 1] += w / w.sum()
     return score
+
+
+# ---------------------------------------------------------------------------
+# Layer importance ("Layer Importance Heuristic") and the two-level allocation
+# ---------------------------------------------------------------------------
+
+def layer_similarity(X_in: np.ndarray, X_out: np.ndarray) -> Tuple[float, np.ndarray]:
+    """Cosine between the input and the output hidden state of a layer, token by token, and its mean
+    over the prompt: the heuristic the paper adopts for layer importance ("Layer Importance
+    Heuristic").  X_in, X_out: [T, H].  Zero rows are handled as in head_similarity (norm product
+    clamped from below by COS_EPS).  Importance follows as for heads: 1 - (mean + 1) / 2
+    (kv_importance with G = 1)."""
+    A = np.asarray(X_in, dtype=np.float64)
+    Bm = np.asarray(X_out, dtype=np.float64)
+    if A.ndim != 2 or A.shape != Bm.shape or A.shape[0] < 1:
+        raise ValueError("X_in and X_out must both be [T, H] with T >= 1")
+    cos = np.empty(A.shape[0], dtype=np.float64)
+    for t in range(A.shape[0]):
+        denom = max(float(np.linalg.norm(A[t]) * np.linalg.norm(Bm[t])), COS_EPS)
+        cos[t] = float(A[t] @ Bm[t]) / denom
+    return float(cos.mean()), cos
+
+
+def alloc_two_level(layer_importance: Sequence[float], head_importance: np.ndarray, global_budget: int,
+                    lo: int, hi: int, t: float, r: float) -> List[int]:
+    """Layer pool first, head pool second ("Layer Importance Heuristic" + "Memory Allocation").
+
+    The paper obtains importances for layers and for the KV caches inside a layer, and prints
+    Algorithm 2 for the caches of one layer; how the layer importances become layer pools is not
+    stated.  Reading taken, built only from the two rules already defined here:
+      1. layer pools: alloc_proportional over the L layer importances with the global budget and
+         the bounds [Hkv*lo, Hkv*hi] (so every layer can give each of its caches between lo and hi);
+      2. inside a layer: the pool is split equally over its Hkv caches, the remainder going one
+         token each to the most important caches first (ties: lower index); then Algorithm 2
+         (alloc_threshold) with threshold t and reduction fraction r moves memory from the caches
+         below the threshold to the most important ones of that layer.
+    head_importance: [L, Hkv].  Returns L*Hkv budgets, layer-major.  Each layer's budgets sum to
+    its pool and all budgets sum to global_budget; the bounds lo/hi constrain the pools, not the
+    budgets Algorithm 2 produces (it does not clip, see alloc_threshold).
+    """
+    himp = np.asarray(head_importance, dtype=np.float64)
+    L, Hkv = himp.shape
+    if len(layer_importance) != L:
+        raise ValueError("one importance per layer expected")
+    pools = alloc_proportional(layer_importance, global_budget, Hkv * lo, Hkv * hi)
+    out: List[int] = []
+    for l in range(L):
+        base, rem = divmod(pools[l], Hkv)
+        order = sorted(range(Hkv), key=lambda i: (-himp[l, i], i))
+        size = [base] * Hkv
+        for i in order[:rem]:
+            size[i] += 1
+        out.extend(alloc_threshold(himp[l].tolist(), size, t, r))
+    return out
 

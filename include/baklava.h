@@ -286,6 +286,36 @@ int baklava_profile_similarity(const void* q, const void* k, const void* v, int3
                                void* stream);
 
 /*
+ * "Layer Importance Heuristic": the cosine between the input and the output hidden state of a layer,
+ * token by token, and its mean over the prompt, for n_seq (layer, prompt) pairs at once.
+ * x_in, x_out DEVICE bf16 [n_seq, T, hidden], 16-byte aligned, hidden a multiple of 8; dtype must be
+ * BAKLAVA_BF16.  cos_out DEVICE fp32 [n_seq, T] or NULL; sim_out DEVICE fp32 [n_seq].  Zero rows as
+ * in baklava_profile_similarity.  Layer importance follows with baklava_kv_importance (Hq = Hkv).
+ * workspace DEVICE, at least baklava_layer_workspace_bytes(n_seq, T) bytes, 16-byte aligned.
+ * Enqueues two kernels on `stream`; deterministic.
+ * Errors: EINVAL, ECAPACITY (workspace too small), EHIP.
+ */
+size_t baklava_layer_workspace_bytes(int32_t n_seq, int32_t T);
+int baklava_layer_similarity(const void* x_in, const void* x_out, int32_t n_seq, int32_t T, int32_t hidden,
+                             int32_t dtype, float* cos_out, float* sim_out, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * Two-level allocation (host only): layer pools from the layer importances by the proportional
+ * rule of baklava_alloc_proportional (bounds Hkv*lo .. Hkv*hi per layer, exact sum), then inside
+ * each layer an equal split of the pool (remainder to the most important caches first, ties to the
+ * lower index) followed by Algorithm 2 (baklava_alloc_threshold) with threshold t and fraction r.
+ * The paper gives importances for layers and for the caches of a layer and Algorithm 2 for the
+ * latter; how layer importances become pools is this library's reading.
+ * layer_importance HOST [L]; head_importance HOST [L * Hkv]; budget_out HOST [L * Hkv]: each
+ * layer's budgets sum to its pool, all of them to global_budget.
+ * Errors: those of the two allocators.
+ */
+int baklava_alloc_two_level(const double* layer_importance, const double* head_importance, int32_t L,
+                            int32_t Hkv, int64_t global_budget, int32_t lo, int32_t hi, double t, double r,
+                            int32_t* budget_out);
+
+/*
  * Attention scores of a whole prompt at once, for the eviction that precedes the decode loop
  * (f_evict of Eqs. 5-6 applied to a prefilled cache with the accumulated-attention policy):
  * score_j = sum over the Hq/Hkv query heads of the KV head and over the prompt tokens t >= j of the

@@ -29,7 +29,8 @@ EXPORTS = [
     "baklava_create",
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
-    "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance", "baklava_prefill_scores",
+    "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance", "baklava_prefill_scores", "baklava_layer_workspace_bytes", "baklava_layer_similarity",
+    "baklava_alloc_two_level",
 ]
 
 
@@ -96,11 +97,18 @@ def lib() -> C.CDLL:
     L.baklava_profile_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_size_t, C.c_void_p]
+    L.baklava_layer_workspace_bytes.restype = C.c_size_t
+    L.baklava_layer_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    L.baklava_layer_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.baklava_alloc_two_level.argtypes = [f64p, f64p, C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32,
+                                          C.c_double, C.c_double, i32p]
     L.baklava_prefill_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.baklava_kv_importance.argtypes = [f64p, C.c_int32, C.c_int32, C.c_int32, f64p]
     for name in EXPORTS:
-        if name not in ("baklava_strerror", "baklava_workspace_bytes", "baklava_profile_workspace_bytes"):
+        if name not in ("baklava_strerror", "baklava_workspace_bytes", "baklava_profile_workspace_bytes",
+                        "baklava_layer_workspace_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -334,4 +342,37 @@ def prefill_scores(q, k_plane, lse, score_plane, batch: int, Hq: int, Hkv: int, 
     _check(lib().baklava_prefill_scores(q.data_ptr(), k_plane.data_ptr(), lse.data_ptr(),
                                         row_off.data_ptr() if row_off is not None else None, batch, Hq, Hkv, T, 128,
                                         BF16, score_plane.data_ptr(), _stream_ptr(stream)), "baklava_prefill_scores")
+
+
+def alloc_two_level(layer_importance, head_importance, global_budget: int, lo: int, hi: int, t: float, r: float):
+    """baklava_alloc_two_level: head_importance [L, Hkv] -> list of L * Hkv budgets (host only)."""
+    himp = np.ascontiguousarray(head_importance, dtype=np.float64)
+    L, Hkv = himp.shape
+    limp = np.ascontiguousarray(layer_importance, dtype=np.float64)
+    if limp.size != L:
+        raise ValueError("one importance per layer expected")
+    out = np.zeros(L * Hkv, dtype=np.int32)
+    _check(lib().baklava_alloc_two_level(_p(limp, C.c_double), _p(himp.reshape(-1), C.c_double), L, Hkv,
+                                         int(global_budget), lo, hi, float(t), float(r), _p(out, C.c_int32)),
+           "baklava_alloc_two_level")
+    return out.tolist()
+
+
+def layer_similarity(x_in, x_out, want_cos: bool = True, stream=None):
+    """baklava_layer_similarity on torch device tensors [n_seq, T, hidden] (bf16).
+    Returns (sim [n_seq], cos [n_seq, T] or None) as torch fp32 device tensors."""
+    import torch
+    n_seq, T, hidden = x_in.shape
+    if x_out.shape != x_in.shape or x_in.dtype != torch.bfloat16 or x_out.dtype != torch.bfloat16:
+        raise ValueError("two bf16 tensors of equal shape expected")
+    if not (x_in.is_contiguous() and x_out.is_contiguous()):
+        raise ValueError("contiguous tensors expected")
+    sim = torch.empty((n_seq,), dtype=torch.float32, device=x_in.device)
+    cos = torch.empty((n_seq, T), dtype=torch.float32, device=x_in.device) if want_cos else None
+    nbytes = int(lib().baklava_layer_workspace_bytes(n_seq, T))
+    ws = torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=x_in.device)
+    _check(lib().baklava_layer_similarity(x_in.data_ptr(), x_out.data_ptr(), n_seq, T, hidden, BF16,
+                                          cos.data_ptr() if want_cos else None, sim.data_ptr(), ws.data_ptr(), nbytes,
+                                          _stream_ptr(stream)), "baklava_layer_similarity")
+    return sim, cos
 

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libbaklava.so")
 
-SOURCES = ["host_alloc.cpp", "api.hip", "decode_valu.hip", "decode_mfma.hip", "compact.hip", "profile.hip", "prefill.hip", "probe.hip"]
+SOURCES = ["host_alloc.cpp", "api.hip", "decode_valu.hip", "decode_mfma.hip", "compact.hip", "profile.hip", "prefill.hip", "layer.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -554,6 +554,26 @@ extern "C" int baklava_profile_similarity(const void* q, const void* k, const vo
   return BAKLAVA_OK;
 }
 
+extern "C" size_t baklava_layer_workspace_bytes(int32_t n_seq, int32_t T) {
+  if (n_seq <= 0 || T <= 0) return 0;
+  return align256((size_t)n_seq * (((size_t)T + 15) / 16) * sizeof(float));  // 16 rows per workgroup
+}
+
+extern "C" int baklava_layer_similarity(const void* x_in, const void* x_out, int32_t n_seq, int32_t T,
+                                        int32_t hidden, int32_t dtype, float* cos_out, float* sim_out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x_in || !x_out || !sim_out || !workspace) return BAKLAVA_EINVAL;
+  if (n_seq <= 0 || T <= 0 || hidden <= 0 || hidden % 8 || dtype != BAKLAVA_BF16) return BAKLAVA_EINVAL;
+  if (((uintptr_t)x_in | (uintptr_t)x_out | (uintptr_t)workspace) & 15) return BAKLAVA_EINVAL;
+  if (((uintptr_t)sim_out | (uintptr_t)cos_out) & 3) return BAKLAVA_EINVAL;
+  if ((int64_t)n_seq * (((int64_t)T + 15) / 16) > INT32_MAX) return BAKLAVA_EINVAL;
+  if (workspace_bytes < baklava_layer_workspace_bytes(n_seq, T)) return BAKLAVA_ECAPACITY;
+  if (!hip_ok(launch_layer_similarity(x_in, x_out, n_seq, T, hidden, cos_out, sim_out,
+                                      reinterpret_cast<float*>(workspace), (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
 extern "C" int baklava_prefill_scores(const void* q, const void* k, const float* lse, const int64_t* row_off,
                                       int32_t batch, int32_t Hq, int32_t Hkv, int32_t T, int32_t D,
                                       int32_t dtype, float* score_out, void* stream) {

@@ -126,6 +126,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s)
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
                                      int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
                                      hipStream_t s);
+hipError_t launch_layer_similarity(const void* x_in, const void* x_out, int n_seq, int T, int hidden,
+                                   float* cos_out, float* sim_out, float* tile_sum, hipStream_t s);
 hipError_t launch_prefill_scores(const void* q, const void* k, const float* lse, const int64_t* row_off,
                                  int batch, int Hq, int Hkv, int T, float* score, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s);

@@ -165,6 +165,29 @@ extern "C" int baklava_kv_importance(const double* similarity_host, int32_t L, i
   return BAKLAVA_OK;
 }
 
+// Layer pools by the proportional rule, then an equal split and Algorithm 2 inside each layer.
+extern "C" int baklava_alloc_two_level(const double* layer_importance, const double* head_importance, int32_t L,
+                                       int32_t Hkv, int64_t global_budget, int32_t lo, int32_t hi, double t,
+                                       double r, int32_t* budget_out) {
+  if (!layer_importance || !head_importance || !budget_out || L <= 0 || Hkv <= 0) return BAKLAVA_EINVAL;
+  if (lo < 0 || hi < lo || (int64_t)Hkv * hi > INT32_MAX) return BAKLAVA_EINVAL;
+  std::vector<int32_t> pools(L);
+  int st = baklava_alloc_proportional(layer_importance, L, global_budget, Hkv * lo, Hkv * hi, pools.data());
+  if (st != BAKLAVA_OK) return st;
+  std::vector<int32_t> size(Hkv), order(Hkv);
+  for (int32_t l = 0; l < L; ++l) {
+    const double* imp = head_importance + (int64_t)l * Hkv;
+    const int32_t base = pools[l] / Hkv, rem = pools[l] % Hkv;
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return imp[a] > imp[b]; });
+    std::fill(size.begin(), size.end(), base);
+    for (int32_t i = 0; i < rem; ++i) size[order[i]] += 1;
+    st = baklava_alloc_threshold(imp, Hkv, size.data(), t, r, budget_out + (int64_t)l * Hkv);
+    if (st != BAKLAVA_OK) return st;
+  }
+  return BAKLAVA_OK;
+}
+
 // Split-K schedule: runs of equal length over each cache's capacity, in launch order.
 extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int32_t L,
                                      int32_t caches_per_layer, int32_t chunk, int32_t target_items,

@@ -1,0 +1,80 @@
+"""GPU parity: baklava_layer_similarity against the oracle, row by row and for the mean."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import baklava_oracle as O
+from paper_2502_13176_amd import binding as B
+from paper_2502_13176_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of three dot products over `hidden` exact bf16 products each: relative error
+# of a sum of n terms ~ sqrt(n) * 2^-24 typical, n * 2^-24 worst case; the cosine is a ratio of such
+# sums.  Bound taken: 2e-5 absolute per row for hidden <= 8192 (measured ~3e-7), 2e-6 for the mean.
+COS_TOL = 2e-5
+MEAN_TOL = 2e-6
+
+
+def _h():
+    import gpu_harness
+    return gpu_harness
+
+
+def run_case(a_bits, b_bits):
+    H = _h()
+    dev = torch.device("cuda:0")
+    a, b = H.to_device_storage(a_bits, "bf16", dev), H.to_device_storage(b_bits, "bf16", dev)
+    sim, cos = B.layer_similarity(a, b)
+    sim2, none = B.layer_similarity(a, b, want_cos=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(sim, sim2)
+    a64, b64 = synth.storage_to_f64(a_bits, "bf16"), synth.storage_to_f64(b_bits, "bf16")
+    sim, cos = sim.cpu().numpy().astype(np.float64), cos.cpu().numpy().astype(np.float64)
+    for s in range(a64.shape[0]):
+        want_mean, want_cos = O.layer_similarity(a64[s], b64[s])
+        assert np.max(np.abs(cos[s] - want_cos)) <= COS_TOL
+        assert abs(sim[s] - want_mean) <= MEAN_TOL
+    return sim, cos
+
+
+@pytest.mark.parametrize("n_seq,T,hidden", [(1, 1, 8), (2, 15, 64), (1, 16, 520), (3, 17, 4096), (1, 100, 4104),
+                                            (2, 33, 8192), (1, 5, 12288)])
+def test_shapes_around_every_tile_boundary(n_seq, T, hidden):
+    rng = np.random.Generator(np.random.PCG64(9900 + T + hidden))
+    a = synth.payload(rng, (n_seq, T, hidden), "bf16")
+    b = synth.payload(rng, (n_seq, T, hidden), "bf16")
+    run_case(a, b)
+
+
+def test_residual_stream_shaped_rows_and_special_rows():
+    """Output = input + a small update (what a transformer layer does), from nearly unchanged to
+    strongly changed; identical, opposite and zero rows."""
+    rng = np.random.Generator(np.random.PCG64(9950))
+    T, hidden = 64, 4096
+    x = rng.standard_normal((4, T, hidden), dtype=np.float32)
+    upd = rng.standard_normal((4, T, hidden), dtype=np.float32)
+    eps = np.array([0.01, 0.1, 1.0, 10.0], dtype=np.float32)[:, None, None]
+    a = synth.f32_to_bf16_bits(x)
+    b = synth.f32_to_bf16_bits(x + eps * upd)
+    b[0, 0] = a[0, 0]                       # identical row
+    b[0, 1] = a[0, 1] ^ 0x8000              # every element negated
+    b[0, 2] = 0                             # zero output row
+    sim, cos = run_case(a, b)
+    assert abs(cos[0, 0] - 1.0) <= 1e-6 and abs(cos[0, 1] + 1.0) <= 1e-6 and cos[0, 2] == 0.0
+    assert np.all(np.diff(sim[1:]) < 0)     # larger updates, lower similarity
+    imp = B.kv_importance(sim[None, :], 1, 4, 4)        # layer importance: the same complement, no grouping
+    assert np.allclose(imp, 1.0 - (sim + 1.0) / 2.0, rtol=0, atol=1e-15)
+
+
+def test_error_paths():
+    dev = torch.device("cuda:0")
+    a = torch.zeros((1, 4, 64), dtype=torch.bfloat16, device=dev)
+    sim = torch.zeros((1,), dtype=torch.float32, device=dev)
+    ws = torch.zeros((256,), dtype=torch.uint8, device=dev)
+    L = B.lib()
+    assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 60, B.BF16, None, sim.data_ptr(), ws.data_ptr(), 256, None) == B.EINVAL
+    assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 64, B.F32, None, sim.data_ptr(), ws.data_ptr(), 256, None) == B.EINVAL
+    assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 64, B.BF16, None, sim.data_ptr(), ws.data_ptr(), 0, None) == B.ECAPACITY
+    assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 64, B.BF16, None, sim.data_ptr(), ws.data_ptr(), 256, None) == B.OK
+    torch.cuda.synchronize()

@@ -210,3 +210,26 @@ def test_profile_workspace_bytes():
     assert B.profile_workspace_bytes(1, 4, 128) == 256
     assert B.profile_workspace_bytes(2, 32, 8192) == 2 * 32 * 64 * 4
     assert B.profile_workspace_bytes(0, 4, 128) == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_two_level_allocation_matches_oracle(seed):
+    rng = np.random.default_rng(500 + seed)
+    L, Hkv = int(rng.integers(1, 40)), int(rng.integers(1, 9))
+    limp = rng.uniform(0.01, 1.0, L)
+    himp = np.round(rng.uniform(0.0, 1.0, (L, Hkv)), 2) if seed % 3 == 0 else rng.uniform(0.0, 1.0, (L, Hkv))
+    lo, hi = 64, 40000
+    Bt = int(rng.integers(L * Hkv * lo, L * Hkv * hi + 1))
+    t, r = float(rng.random()), float(rng.random())
+    got = B.alloc_two_level(limp, himp, Bt, lo, hi, t, r)
+    assert got == O.alloc_two_level(limp, himp, Bt, lo, hi, t, r)
+    assert sum(got) == Bt
+
+
+def test_two_level_allocation_errors():
+    with pytest.raises(B.BaklavaError) as e:
+        B.alloc_two_level([1.0, 1.0], [[0.5, 0.5], [0.5, 0.5]], 10, 64, 100, 0.5, 0.5)      # below L*Hkv*lo
+    assert e.value.status == B.EINFEASIBLE
+    with pytest.raises(B.BaklavaError) as e:
+        B.alloc_two_level([1.0, 1.0], [[0.5, 0.5], [0.5, 0.5]], 400, 64, 200, 0.5, 1.5)
+    assert e.value.status == B.EINVAL

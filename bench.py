@@ -34,7 +34,7 @@ def parse_args():
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector-ALU, 2 MFMA")
     ap.add_argument("--chunk", type=int, default=0, help="rows per split-K work item (0 = library default)")
     ap.add_argument("--no-profiling-row", action="store_true",
-                    help="skip the measurements of the one-time profiling kernel and of the prompt-wide scores")
+                    help="skip the measurements of the profiling, prompt-score and layer-importance kernels")
     ap.add_argument("--target-items-whole", type=int, default=-1,
                     help="work items per whole-model launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--target-items", type=int, default=-1,
@@ -249,9 +249,68 @@ def prefill_row(torch, B, synth, device, with_cpu_baseline, T=32768, reps=5):
     return row
 
 
-def read_traffic(workload, mode):
-    """HBM bytes per launch of the dominant kernel, from the committed counter summary (if any)."""
-    path = os.path.join(ROOT, "profiles", f"decode_partial_mfma_{workload}_{mode}_pmc.txt")
+def layer_row(torch, B, synth, device, with_cpu_baseline, n_layers=32, T=8192, hidden=4096, reps=10):
+    """The layer-importance kernel on the hidden states of a T-token prompt at the input and output of
+    every layer of a LLaMA-3-8B-shaped model: 2 * hidden * 2 algorithmic bytes per (layer, token)."""
+    import numpy as np
+    gen = torch.Generator(device=device)
+    gen.manual_seed(999)
+    a = torch.randn((n_layers, T, hidden), generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+    b = (a.float() + 0.3 * torch.randn((n_layers, T, hidden), generator=gen, device=device,
+                                       dtype=torch.float32)).to(torch.bfloat16)       # residual stream + update
+    sim = torch.empty((n_layers,), dtype=torch.float32, device=device)
+    nbytes = int(B.lib().baklava_layer_workspace_bytes(n_layers, T))
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run():
+        st = B.lib().baklava_layer_similarity(a.data_ptr(), b.data_ptr(), n_layers, T, hidden, B.BF16, None,
+                                              sim.data_ptr(), ws.data_ptr(), nbytes, stream)
+        if st != B.OK:
+            raise RuntimeError(f"baklava_layer_similarity: status {st}")
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes_alg = 2 * n_layers * T * hidden * 2
+    row = {
+        "what": "layer importance heuristic: token-wise cosine between each layer's input and output hidden state, mean per layer",
+        "config": {"workload": f"LLaMA-3-8B-shaped: {n_layers} layers, hidden {hidden}, prompt of {T} tokens, bf16"},
+        "us": round(ms * 1e3, 1),
+        "roofline": {"bound": "hbm", "kernel": "layer_cosine_kernel", "achieved": round(nbytes_alg / ms / 1e6, 1),
+                     "peak": 8000.0, "unit": "GB/s", "frac": round(nbytes_alg / ms / 1e6 / 8000.0, 4),
+                     "traffic": read_traffic(None, None, "layer_cosine_kernel_llama_32layers_T8192.txt")
+                     if (n_layers, T, hidden) == (32, 8192, 4096) else None,
+                     "algorithmic_bytes_per_launch": nbytes_alg},
+    }
+    if with_cpu_baseline:
+        import time
+        from oracle import baklava_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        a64 = synth.storage_to_f64(a[0].view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        b64 = synth.storage_to_f64(b[0].view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
+        t0 = time.perf_counter()
+        want, _ = O.layer_similarity(a64, b64)
+        dt = time.perf_counter() - t0
+        row["cpu_baseline"] = {"value": round(2 * T * hidden * 2 / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads),
+                               "kind": "oracle", "sample": f"fp64 oracle layer_similarity on 1 of {n_layers} layers ({dt:.2f} s), "
+                                                            "bytes counted as stored (bf16)"}
+        row["abs_error_vs_oracle_on_sample"] = abs(float(sim[0]) - want)
+    return row
+
+
+def read_traffic(workload, mode, name=None):
+    """HBM bytes per launch of a kernel, from the committed counter summary (if any)."""
+    path = os.path.join(ROOT, "profiles", name or f"decode_partial_mfma_{workload}_{mode}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -411,6 +470,7 @@ def main():
         # the next row of the path after the decode loop's own: the one-time profiling kernel
         result["profiling_kernel"] = profiling_row(torch, B, arena.device, not args.no_cpu_baseline)
         result["prefill_scores"] = prefill_row(torch, B, synth, arena.device, not args.no_cpu_baseline)
+        result["layer_importance"] = layer_row(torch, B, synth, arena.device, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
     arena.close()

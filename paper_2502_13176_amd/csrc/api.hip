@@ -23,7 +23,7 @@ inline bool hip_ok(hipError_t e) {
 
 constexpr int kMinChunk = 256;
 constexpr int kSizingChunk = 256;  // the workspace is sized for chunks of at least this many rows
-constexpr int kDefaultChunk = 512;        // launches over part of the model (a few hundred MB)
+constexpr int kDefaultChunk = 512;        // launches over part of the model: shortest run (the item target lengthens it)
 constexpr int kDefaultChunkWhole = 256;   // launches over the whole model: shortest run; longer ones come from the item target
 constexpr int kWholeItemsPerCu = 5;       // whole-model launches aim at this many work items per compute unit
 constexpr int kMaxChunk = 1 << 22; // row offsets inside a work item stay below 2^32 bytes
@@ -38,7 +38,7 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 
 struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
-  size_t items[2], cib[2], multi[2];
+  size_t items[2], multi[2];
   size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer;
   size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, stash_off, total;
   int64_t n_segs, halo_rows;
@@ -88,8 +88,7 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   size_t o = 0;
   for (int k = 0; k < 2; ++k) {
     w.items[k] = o;   o = align256(o + (size_t)w.max_items * sizeof(Item));
-    w.cib[k] = o;     o = align256(o + (size_t)(n_caches + 1) * 4);
-    w.multi[k] = o;   o = align256(o + (size_t)n_caches * 4);
+    w.multi[k] = o;   o = align256(o + (size_t)n_caches * sizeof(MultiCache));
   }
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
   w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
@@ -156,7 +155,8 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   if (st != BAKLAVA_OK) return st;
   static_assert(sizeof(baklava_work_item) == sizeof(Item), "work item layouts must match");
   // cache -> first partial slot, and the caches that need the combine kernel (in launch order)
-  std::vector<int32_t> cib(ctx->n_caches + 1, 0), multi, multi_begin(ctx->d.L + 1, 0);
+  std::vector<int32_t> cib(ctx->n_caches + 1, 0), multi_begin(ctx->d.L + 1, 0);
+  std::vector<MultiCache> multi;
   int32_t max_count = 0;
   for (int64_t i = 0; i < n_items; ++i) {
     const baklava_work_item& it = items[i];
@@ -164,7 +164,7 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
     if (it.start == 0) {
       cib[it.cache] = it.slot;
       if (it.nsplit > 1) {
-        multi.push_back(it.cache);
+        multi.push_back(MultiCache{it.cache, it.slot, it.slot + it.nsplit, 0});
         multi_begin[it.cache / ctx->cpl + 1] += 1;
       }
     }
@@ -174,9 +174,8 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
   if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.items[which], items.data(), (size_t)n_items * sizeof(Item),
                         hipMemcpyHostToDevice)) ||
-      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.cib[which], cib.data(), cib.size() * 4, hipMemcpyHostToDevice)) ||
       (!multi.empty() &&
-       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi[which], multi.data(), multi.size() * 4, hipMemcpyHostToDevice))))
+       !hip_ok(hipMemcpy(ctx->ws + ctx->plan.multi[which], multi.data(), multi.size() * sizeof(MultiCache), hipMemcpyHostToDevice))))
     return BAKLAVA_EHIP;
   ctx->sched[which].cib.swap(cib);
   ctx->sched[which].multi_begin.swap(multi_begin);
@@ -208,7 +207,6 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   // Slots are numbered cache by cache and the launch order only permutes caches inside a layer
   // (schedule 0), so the launch-ordered table of a layer range is the slice [i0, i1).
   p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]) + i0;
-  p.cache_item_begin = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.cib[which]);
   p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
   p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
@@ -218,7 +216,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   p.score = ctx->d.score;
   p.pos = ctx->d.pos;
   const int32_t m0 = sc.multi_begin[layer_begin], m1 = sc.multi_begin[layer_begin + layer_count];
-  p.multi = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.multi[which]) + m0;
+  p.multi = reinterpret_cast<const MultiCache*>(ctx->ws + ctx->plan.multi[which]) + m0;
   p.k_new = k_new; p.v_new = v_new;
   p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
   p.cache_begin = (int32_t)c0;

@@ -40,6 +40,12 @@ struct CompactInfo {
   int32_t pad;
 };
 
+// A cache that the combine kernel serves, with its partial slots [slot_begin, slot_end): one
+// 16-byte record, so that the kernel needs a single load before it can fetch the partials.
+struct MultiCache {
+  int32_t c, slot_begin, slot_end, pad;
+};
+
 struct DecodeParams {
   void* k;
   void* v;
@@ -48,7 +54,6 @@ struct DecodeParams {
   const int64_t* off;
   int32_t* len;
   const Item* items;               // work items of the launched range, in launch order
-  const int32_t* cache_item_begin; // [n_caches + 1], absolute item index
   float* part_o;                   // [n_items, G, D] un-normalised partial outputs
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
   float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
@@ -61,7 +66,7 @@ struct DecodeParams {
   const int32_t* cap;
   float* score;
   int32_t* pos;
-  const int32_t* multi;            // caches of the launched range that have more than one work item
+  const MultiCache* multi;         // caches of the launched range that have more than one work item
   const void* k_new;               // fused append: [caches of the range, D] rows to add first
   const void* v_new;
   int32_t G, Hq, Hkv, batch;

@@ -1,6 +1,6 @@
 // Shared head and tail of the two attention kernels: the fused append of the new row, and the
-// end of a work item (merge of the workgroup's wavefronts, publication of the split partial, and
-// the combine done by whichever work item of a cache finishes last).
+// end of a work item (merge of the workgroup's wavefronts, then either the finished output of a
+// cache that has a single work item or the split partial the combine kernel reads).
 #ifndef BAKLAVA_DECODE_TAIL_H
 #define BAKLAVA_DECODE_TAIL_H
 

@@ -195,11 +195,12 @@ template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
   constexpr int GROUPS = 256 / D;
   const int G = p.G;
-  const int c = p.multi[blockIdx.x / G];
+  const MultiCache mc = p.multi[blockIdx.x / G];
+  const int c = mc.c;
   const int g = blockIdx.x % G;
   const int tid = threadIdx.x;
   const int d = tid % D, grp = tid / D;
-  const int ib = p.cache_item_begin[c], ie = p.cache_item_begin[c + 1];
+  const int ib = mc.slot_begin, ie = mc.slot_end;
   float m = kNegInf, l = 0.f, o = 0.f;
 #pragma unroll 8
   for (int s = ib + grp; s < ie; s += GROUPS) {

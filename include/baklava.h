@@ -103,7 +103,8 @@ int baklava_layout(const int32_t* budget, int32_t L, int32_t Hkv, int32_t batch,
  * otherwise) that would have more than max(target_items, caches in the unit) work items gets
  * longer runs: the smallest multiple of 64 that brings it to that many items -- e.g. one
  * workgroup per compute unit, so that a launch is one even wave of workgroups -- after which the
- * runs inside each cache are made equal (rounded up to 64 rows) without adding an item.
+ * runs inside each cache are made equal (rounded up to 64 rows) without adding an item.  A run
+ * never exceeds 2^22 rows, whatever the target.
  * off_host HOST int64 [L*caches_per_layer], cap_host HOST int32 [same]; chunk a multiple of 64,
  * >= 256; items_out HOST [max_items] or NULL (count only); n_items_out HOST scalar.
  * Errors: EINVAL, ECAPACITY (more than max_items work items; n_items_out still receives the count).

@@ -223,7 +223,8 @@ extern "C" int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap
         const int64_t mid = (lo + hi) / 2;
         if (items_at(mid * 64) > target) lo = mid; else hi = mid;
       }
-      const int64_t unit_run = hi * 64;
+      // a work item never spans more than 2^22 rows (the kernels address its rows with 32-bit byte offsets)
+      const int64_t unit_run = std::min<int64_t>(hi * 64, int64_t(1) << 22);
       // inside a cache the runs are then made equal: no run grows, the count stays
       for (int64_t c = c0; c < c1; ++c) {
         const int64_t n = runs(c, unit_run);

@@ -233,3 +233,13 @@ def test_two_level_allocation_errors():
     with pytest.raises(B.BaklavaError) as e:
         B.alloc_two_level([1.0, 1.0], [[0.5, 0.5], [0.5, 0.5]], 400, 64, 200, 0.5, 1.5)
     assert e.value.status == B.EINVAL
+
+
+def test_schedule_runs_never_exceed_the_row_limit():
+    """One enormous cache and a target of one item: the run stops at 2^22 rows."""
+    cap = np.array([(1 << 24) + 100, 300], dtype=np.int32)
+    off = np.array([0, (1 << 24) + 100], dtype=np.int64)
+    items = B.plan_schedule(off, cap, 1, 2, 256, False, target_items=1)
+    big = [it for it in items if it[0] == 0]
+    assert len(big) == 5 and max(it[2] for it in big) <= 1 << 22          # ceil(cap / 2^22) runs, made equal
+    assert sum(it[2] for it in big) == cap[0] and big[0][2] == (-(-int(cap[0]) // 5) + 63) // 64 * 64

@@ -128,7 +128,7 @@ struct baklava_ctx {
   int32_t target_items_whole;  // > 0: the same for launches over the whole model
   struct Schedule {
     int32_t chunk = 0;
-    int32_t max_count = 0;             // longest work item, rows
+    std::vector<int32_t> max_count;    // layer -> longest work item of the layer, rows
     std::vector<int32_t> cib;          // cache -> first item
     std::vector<int32_t> multi_begin;  // layer -> first entry of the list of multi-item caches
   } sched[2];                          // 0: layer sub-range launches, 1: whole-model launches
@@ -157,10 +157,10 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   // cache -> first partial slot, and the caches that need the combine kernel (in launch order)
   std::vector<int32_t> cib(ctx->n_caches + 1, 0), multi_begin(ctx->d.L + 1, 0);
   std::vector<MultiCache> multi;
-  int32_t max_count = 0;
+  std::vector<int32_t> max_count(ctx->d.L, 0);
   for (int64_t i = 0; i < n_items; ++i) {
     const baklava_work_item& it = items[i];
-    max_count = std::max(max_count, it.count);
+    max_count[it.cache / ctx->cpl] = std::max(max_count[it.cache / ctx->cpl], it.count);
     if (it.start == 0) {
       cib[it.cache] = it.slot;
       if (it.nsplit > 1) {
@@ -180,7 +180,7 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   ctx->sched[which].cib.swap(cib);
   ctx->sched[which].multi_begin.swap(multi_begin);
   ctx->sched[which].chunk = chunk;
-  ctx->sched[which].max_count = max_count;
+  ctx->sched[which].max_count.swap(max_count);
   return BAKLAVA_OK;
 }
 
@@ -249,7 +249,11 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
   if (fused)
     for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
-  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, sc.max_count, s))) return BAKLAVA_EHIP;
+  if (p.track) {
+    const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
+                                              sc.max_count.begin() + layer_begin + layer_count);
+    if (!hip_ok(launch_score_update(p, i1 - i0, longest, s))) return BAKLAVA_EHIP;
+  }
   return BAKLAVA_OK;
 }
 

@@ -468,9 +468,14 @@ def main():
     result["stream_probe"] = stream_probe(torch, B, arena.device)
     if not args.no_profiling_row:
         # the next row of the path after the decode loop's own: the one-time profiling kernel
-        result["profiling_kernel"] = profiling_row(torch, B, arena.device, not args.no_cpu_baseline)
-        result["prefill_scores"] = prefill_row(torch, B, synth, arena.device, not args.no_cpu_baseline)
-        result["layer_importance"] = layer_row(torch, B, synth, arena.device, not args.no_cpu_baseline)
+        # (each guarded: the line with the main metric is printed whatever happens to these)
+        for key, fn in (("profiling_kernel", lambda: profiling_row(torch, B, arena.device, not args.no_cpu_baseline)),
+                        ("prefill_scores", lambda: prefill_row(torch, B, synth, arena.device, not args.no_cpu_baseline)),
+                        ("layer_importance", lambda: layer_row(torch, B, synth, arena.device, not args.no_cpu_baseline))):
+            try:
+                result[key] = fn()
+            except Exception as exc:  # noqa: BLE001
+                result[key] = {"error": f"{type(exc).__name__}: {exc}"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(arena, w, q, torch, args.cpu_seconds)
     arena.close()

@@ -203,6 +203,17 @@ __global__ __launch_bounds__(256, 2) void profile_attn_kernel(ProfileParams p) {
       const float nm0 = -m_ref[0], nm1 = -m_ref[1];
 #pragma unroll
       for (int sl = 0; sl < 2; ++sl) {
+        // The slab's 16 transposed V operands are fetched before the weights are formed, so that the
+        // LDS latency hides behind the exponentials; every operand serves both column tiles.
+        const unsigned char* tr0 = &lds_v[buf][(sl * 32 + jg * 4 + (n16 >> 2)) * kVStride + (n16 & 3) * 8];
+        bf16x8_t va[8];
+#pragma unroll
+        for (int bb = 0; bb < 8; ++bb) {
+          typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + bb * 32));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + 16 * kVStride + bb * 32));
+          va[bb] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
         // each weight is split into a truncated bf16 high part and a bf16 residual, so the second
         // product keeps ~16 bits of it (one bf16 term alone costs about 1e-3 on a token's cosine)
         u32x4_t ph[2];
@@ -221,18 +232,12 @@ __global__ __launch_bounds__(256, 2) void profile_attn_kernel(ProfileParams p) {
             pl[nt][e + 1] = (__bf16)(p1 - __uint_as_float(u1 & 0xffff0000u));
           }
         }
-        // every transposed V operand is read once for both column tiles
-        const unsigned char* tr0 = &lds_v[buf][(sl * 32 + jg * 4 + (n16 >> 2)) * kVStride + (n16 & 3) * 8];
 #pragma unroll
         for (int bb = 0; bb < 8; ++bb) {
-          typedef __attribute__((address_space(3))) s16x4_t* lds_ptr_t;
-          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + bb * 32));
-          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(tr0 + 16 * kVStride + bb * 32));
-          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[0]), o[0][bb], 0, 0, 0);
-          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, as_bf16x8(ph[1]), o[1][bb], 0, 0, 0);
-          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[0], o[0][bb], 0, 0, 0);
-          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pl[1], o[1][bb], 0, 0, 0);
+          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[bb], as_bf16x8(ph[0]), o[0][bb], 0, 0, 0);
+          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[bb], as_bf16x8(ph[1]), o[1][bb], 0, 0, 0);
+          o[0][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[bb], pl[0], o[0][bb], 0, 0, 0);
+          o[1][bb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[bb], pl[1], o[1][bb], 0, 0, 0);
         }
       }
     }

@@ -126,6 +126,7 @@ struct baklava_ctx {
   int32_t kernel_pref;
   int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
   int32_t target_items_whole;  // > 0: the same for launches over the whole model
+  int32_t n_cus;               // compute units of the device
   struct Schedule {
     int32_t chunk = 0;
     std::vector<int32_t> max_count;    // layer -> longest work item of the layer, rows
@@ -239,7 +240,10 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
     ev1 = ctx->ev[2 * ctx->ev_used + 1];
     if (!hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
   }
-  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, s)
+  const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
+                                            sc.max_count.begin() + layer_begin + layer_count);
+  p.stash_slots = 0;
+  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, longest, i1 - i0 <= ctx->n_cus, s)
                           : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
   if (!hip_ok(e)) return BAKLAVA_EHIP;
   if (ctx->time_kernel) {
@@ -249,11 +253,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
   if (fused)
     for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
-  if (p.track) {
-    const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
-                                              sc.max_count.begin() + layer_begin + layer_count);
-    if (!hip_ok(launch_score_update(p, i1 - i0, longest, s))) return BAKLAVA_EHIP;
-  }
+  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, longest, s))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;
 }
 
@@ -315,6 +315,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       return BAKLAVA_EHIP;
     }
     ctx->target_items = cus;
+    ctx->n_cus = cus;
     // Whole-model launches: runs long enough to amortise the per-item costs, yet enough items for
     // the dispatcher to even out the load over several waves of workgroups.
     ctx->target_items_whole = kWholeItemsPerCu * cus;

@@ -72,6 +72,7 @@ struct DecodeParams {
   int32_t G, Hq, Hkv, batch;
   int32_t cache_begin;             // first cache id of the launched range
   int32_t track;
+  int32_t stash_slots;             // MFMA kernel, score tracking: slabs per wavefront kept in LDS (0: none)
   int32_t fused_append;            // 1: every cache of the range first receives its new row
   int32_t token_pos;
   int32_t row_bytes;
@@ -127,7 +128,9 @@ struct CompactParams {
 
 // Launchers (defined next to their kernels).  All return hipError_t of the launch.
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
-hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s);
+// max_count: longest work item of the launch (rows); one_wave: the launch has at most one workgroup per
+// compute unit, so a workgroup may take the whole LDS (score tracking keeps its logits there)
+hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, int max_count, bool one_wave, hipStream_t s);
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
                                      int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
                                      hipStream_t s);

@@ -27,6 +27,8 @@
 #include "common.h"
 #include "decode_tail.h"
 
+#include <algorithm>
+
 namespace baklava {
 
 namespace {
@@ -62,6 +64,11 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   // K staging; once a slab's A operands are read, the same bytes serve as the [head][row] buffer of
   // the logit stash
   __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWaves * kSlab * kKStride];
+  // Score tracking, launches of one wave of workgroups: every wavefront keeps the logits of its slabs
+  // here ([G][32] floats per slab, p.stash_slots slabs) and writes them out when the work item is
+  // done (or the area is full), so that the stash writes of a launch fall together at its end
+  // instead of being interleaved with the K/V reads, which the memory system handles badly.
+  extern __shared__ __attribute__((aligned(16))) float lds_stash[];
   static_assert(16 * kSlab * 4 <= kSlab * kKStride, "logit buffer fits the K staging area");
 
   const Item it = p.items[blockIdx.x];
@@ -120,6 +127,24 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   // wait counter stall on the prefetches.
   float* lg = nullptr;
   if (p.track && lane < 8 * G) lg = p.logits + (stash0 + (int64_t)it.start * G + lane * 4);
+  float* ring = lds_stash + wave * p.stash_slots * (kSlab * G);
+  int ring_n = 0;         // slabs held in the LDS area
+  int ring_t0 = 0;        // first row of the oldest one; the others follow at kWaves * kSlab rows each
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  auto flush_ring = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int sidx = 0; sidx < ring_n; ++sidx) {
+      const float* src = ring + sidx * (kSlab * G) + lane * 4;
+      float* dst = lg + (ring_t0 + sidx * (kWaves * kSlab)) * G;
+      if (lg) *reinterpret_cast<f32x4_t*>(dst) = *reinterpret_cast<const f32x4_t*>(src);
+      if (lg && lane + 64 < 8 * G) *reinterpret_cast<f32x4_t*>(dst + 256) = *reinterpret_cast<const f32x4_t*>(src + 256);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the area may be written again
+    ring_n = 0;
+  };
 
   // Order of the first loads: K of the first slab, then the query, then V.  The loop's first wait
   // (for K and, on the first pass, the query) then leaves the V loads in flight, and the stream
@@ -187,10 +212,20 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
         for (int i = 0; i < 4; ++i)
           if (t0 + T * 16 + jg * 4 + i >= cnt) x[T * 4 + i] = kNegInf;
     }
-    if (p.track) {
+    if (p.track && p.stash_slots > 0) {
+      // into the LDS area, in the layout of the global stash: one line of 32 rows per head
+      if (ring_n == 0) ring_t0 = t0;
+      float* tl = ring + ring_n * (kSlab * G);
+      if (n16 < G) {
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+          *reinterpret_cast<f32x4_t*>(tl + n16 * kSlab + T * 16 + jg * 4) =
+              f32x4_t{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
+      }
+      if (++ring_n == p.stash_slots) flush_ring();
+    } else if (p.track) {
       // Through LDS from the accumulator layout (lane (g, jg): rows 4jg..4jg+3 of each tile) to
       // one line per head.  Rows past the live length carry -inf and are never read back.
-      typedef float f32x4_t __attribute__((ext_vector_type(4)));
       float* tl = reinterpret_cast<float*>(myk);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();  // the slab's K operands have been read
@@ -256,6 +291,8 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
 #undef BAKLAVA_LOAD_K
 #undef BAKLAVA_LOAD_V
 
+  if (ring_n > 0) flush_ring();
+
   // Sum of the four lanes of a head.
   float l_tot = l_part;
   l_tot += __shfl_xor(l_tot, 16);
@@ -283,10 +320,30 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, hipStream_t s) {
+hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_count, bool one_wave, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
-  if (p.G > 16) return hipErrorInvalidValue;
-  decode_partial_mfma<<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
+  if (p_in.G > 16) return hipErrorInvalidValue;
+  DecodeParams p = p_in;
+  p.stash_slots = 0;
+  size_t dyn = 0;
+  if (p.track && one_wave) {
+    // the whole LDS of a CU minus the static staging areas, split over the wavefronts
+    constexpr int kLdsTotal = 160 * 1024;
+    constexpr int kStatic = kWaves * kSlab * (kVStride + kKStride);
+    const int slot_bytes = kSlab * p.G * 4;
+    const int fit = (kLdsTotal - kStatic - 512) / (kWaves * slot_bytes);
+    const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;  // slabs of the longest item per wavefront
+    p.stash_slots = std::max(1, std::min(fit, need));
+    dyn = (size_t)p.stash_slots * kWaves * slot_bytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal - kStatic - 512);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+  }
+  decode_partial_mfma<<<dim3(n_items), dim3(64 * kWaves), dyn, s>>>(p);
   return hipGetLastError();
 }
 

@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-track", action="store_true", help="do not accumulate attention scores (long workload)")
     ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
+    ap.add_argument("--interval", type=int, default=0,
+                    help="evict every N steps instead of the workload's own interval (capacity = budget + N)")
+    ap.add_argument("--policy", default="score", choices=["score", "streaming"],
+                    help="eviction policy: sink + recent + top scores, or sink + most recent rows")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the extra region in the other launch mode (keeps profiler traces to one mode)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle leg")
@@ -336,10 +340,13 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.interval > 0:
+        w = synth.shrink(w, interval=args.interval, slack=args.interval)
     budgets = synth.budgets_for(w, B.alloc_proportional)
     track = w.scores == "kernel" and not args.no_track
+    policy = B.POLICY_STREAMING if args.policy == "streaming" else B.POLICY_SCORE
     arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack, w.sink, w.recent,
-                    B.POLICY_SCORE, track)
+                    policy, track)
     gen = synth.fill_arena_on_device(arena, w)
     cpl = w.batch * w.Hkv
     lens0 = np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], dtype=np.int32)
@@ -427,7 +434,7 @@ def main():
         "config": {
             "workload": f"{w.name}: {w.L} layers x {w.Hkv} KV heads (G={w.G}), D={w.D}, batch {w.batch}, "
                         f"context {w.ctx}, keep {w.keep_pct}% ({sum(budgets) * w.batch} cached tokens), "
-                        f"compaction every {interval} steps" if interval else
+                        f"compaction every {interval} steps ({args.policy} policy)" if interval else
                         f"{w.name}: attention and appends only",
             "launch_mode": args.mode, "n_caches": arena.n_caches, "kv_bytes_per_step": state["kv_bytes"] // args.steps,
             "compactions_in_timed_region": state["compactions"], "track_scores": bool(track),

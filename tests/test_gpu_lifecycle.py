@@ -81,3 +81,14 @@ def test_grow_from_empty_evict_reset(dtype, D, Hq, Hkv, policy):
                      seed=61, sink=3, recent=0 if policy == B.POLICY_STREAMING else 5, interval=9, slack=9)
     budgets = [40, 300, 270, 17][: w.L * w.Hkv]
     run_from_empty(w, budgets, policy, steps=30, chunks=[256, 512, 1024])
+
+
+@pytest.mark.parametrize("policy", [B.POLICY_STREAMING, B.POLICY_SCORE])
+def test_evict_every_step(policy):
+    """Eviction after every decode step (capacity = budget + 1): under the streaming policy each cache
+    is a sliding window behind its sink rows; under the score policy one middle row leaves per step.
+    Caches that have not reached their budget yet pass through the eviction unchanged."""
+    w = synth.shrink(synth.WORKLOADS["long"], name="every", L=2, Hq=8, Hkv=2, D=128, batch=2, dtype="bf16",
+                     seed=62, sink=3, recent=0 if policy == B.POLICY_STREAMING else 5, interval=1, slack=1)
+    budgets = [12, 45, 30, 8]
+    run_from_empty(w, budgets, policy, steps=60, chunks=[256])

@@ -8,6 +8,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# The pins' own check (test_oracle_mutants.py) runs them in a child process against an oracle with
+# one planted mistake; the child is told which one through this variable.
+if os.environ.get("BAKLAVA_ORACLE_MUTANT"):
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import oracle_mutants
+    oracle_mutants.install(os.environ["BAKLAVA_ORACLE_MUTANT"])
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

@@ -243,3 +243,20 @@ def test_schedule_runs_never_exceed_the_row_limit():
     big = [it for it in items if it[0] == 0]
     assert len(big) == 5 and max(it[2] for it in big) <= 1 << 22          # ceil(cap / 2^22) runs, made equal
     assert sum(it[2] for it in big) == cap[0] and big[0][2] == (-(-int(cap[0]) // 5) + 63) // 64 * 64
+
+
+def test_hand_worked_allocation_examples_through_the_library():
+    """The hand-worked examples that pin the oracle, asked of the C library directly."""
+    assert B.alloc_proportional([7, 4, 8, 5], 24, 1, 7) == [7, 4, 7, 6]
+    assert B.alloc_threshold([0.2, 0.5, 0.5, 0.9], [100] * 4, 0.5, 0.5) == [50, 100, 100, 150]
+    assert B.alloc_threshold([0.1, 0.9, 0.9], [100, 100, 100], 0.5, 0.5) == [50, 150, 100]
+    got = B.alloc_two_level([1.0, 1000.0], np.array([[0.4, 0.4, 0.4], [0.3, 0.9, 0.5]]), 332, 10, 1000, 0.0, 0.5)
+    assert got == [10, 10, 10, 100, 101, 101]
+    rng = np.random.Generator(np.random.PCG64(7))
+    for _ in range(500):                                        # small cases where clipping and leftovers dominate
+        m = int(rng.integers(2, 6))
+        imp = [float(v) for v in rng.integers(1, 9, size=m)]
+        lo = int(rng.integers(0, 4))
+        hi = int(rng.integers(lo + 1, 13))
+        Bt = int(rng.integers(m * lo, m * hi + 1))
+        assert B.alloc_proportional(imp, Bt, lo, hi) == O.alloc_proportional(imp, Bt, lo, hi)

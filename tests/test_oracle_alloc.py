@@ -196,3 +196,41 @@ def test_layout_prefix_sums():
     assert total == 40
     off, cap, total = O.layout([5, 9, 1, 2], L=2, Hkv=2, batch=1, slack=0)
     assert cap == [5, 9, 1, 2] and off == [0, 5, 14, 15] and total == 17
+
+
+def test_leftover_tokens_never_lift_a_head_above_hi():
+    """Shares 24 * [7, 4, 8, 5] / 24 = [7, 4, 8, 5]; hi = 7 clips head 2 and one token is left over.
+    Head 0 sits at hi exactly and may not take it; of heads 1 and 3 the heavier one is next in line."""
+    assert O.alloc_proportional([7, 4, 8, 5], 24, 1, 7) == [7, 4, 7, 6]
+
+
+def test_invariants_on_many_small_cases():
+    """Exact sum, bounds and monotonicity where clipping and leftovers dominate (few heads, tight bounds)."""
+    rng = np.random.Generator(np.random.PCG64(7))
+    for _ in range(3000):
+        m = int(rng.integers(2, 6))
+        imp = [float(v) for v in rng.integers(1, 9, size=m)]
+        lo = int(rng.integers(0, 4))
+        hi = int(rng.integers(lo + 1, 13))
+        B = int(rng.integers(m * lo, m * hi + 1))
+        b = O.alloc_proportional(imp, B, lo, hi)
+        assert sum(b) == B and min(b) >= lo and max(b) <= hi, (imp, B, lo, hi, b)
+        for i in range(m):
+            for j in range(m):
+                if imp[i] < imp[j]:
+                    assert b[i] <= b[j], (imp, B, lo, hi, b)
+                if imp[i] == imp[j]:
+                    assert abs(b[i] - b[j]) <= 1, (imp, B, lo, hi, b)
+
+
+def test_threshold_comparison_is_strict():
+    """Algorithm 2 selects I_i < t: caches whose importance equals the threshold keep their size.
+    I = [0.2, 0.5, 0.5, 0.9], t = 0.5, r = 1/2, 100 rows each: only cache 0 shrinks (by 50), n = 1,
+    k = min(1, 3) = 1, and the most important cache receives the 50 rows."""
+    assert O.alloc_threshold([0.2, 0.5, 0.5, 0.9], [100] * 4, 0.5, 0.5) == [50, 100, 100, 150]
+
+
+def test_threshold_ties_among_receivers_go_to_the_lower_index():
+    """Two equally important caches compete for one receiving place (k = min(1, 2) = 1): the paper
+    does not say who wins; the reading taken is the lower index."""
+    assert O.alloc_threshold([0.1, 0.9, 0.9], [100, 100, 100], 0.5, 0.5) == [50, 150, 100]

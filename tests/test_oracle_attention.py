@@ -198,3 +198,19 @@ def test_score_accumulate_sums_over_group():
     p = np.array([[0.25, 0.75], [0.5, 0.5]])
     s = O.score_accumulate(np.array([1.0, 2.0]), p)
     assert s.tolist() == [1.75, 3.25]
+
+
+def test_eviction_happens_exactly_at_multiples_of_the_interval():
+    """Step t evicts iff t is a multiple of the interval: a cache that starts at its budget b holds
+    b + (t mod interval) rows after step t, and b again after every interval-th step."""
+    rng = np.random.default_rng(5)
+    D, b, interval = 8, 12, 4
+    cache = O.Cache(D)
+    cache.load(rng.standard_normal((b, D)), rng.standard_normal((b, D)), rng.random(b), np.arange(b))
+    for t in range(1, 2 * interval + 2):
+        _, _, kept = O.decode_step(cache, rng.standard_normal((2, D)), rng.standard_normal(D), rng.standard_normal(D),
+                                   100 + t, t, budget=b, sink=2, recent=3, interval=interval, track_scores=True)
+        if t % interval == 0:
+            assert kept is not None and len(kept) == b and cache.n == b
+        else:
+            assert kept is None and cache.n == b + t % interval

@@ -78,3 +78,13 @@ def test_two_level_allocation_invariants():
     # equal split 1500 / 1500, the low cache gives floor(0.5 * 1500) = 750 to the other
     b = O.alloc_two_level([1.0, 3.0], np.array([[0.8, 0.9], [0.2, 0.7]]), 4000, 10, 5000, 0.5, 0.5)
     assert b == [500, 500, 750, 2250]
+
+
+def test_two_level_hand_worked_floor_pool_and_remainder():
+    """Layer importances [1, 1000], 3 caches per layer, lo = 10, global budget 332: layer 0's share
+    (0.33 rows) is lifted to the floor of 3 * lo = 30 rows, layer 1 takes the other 302.  Inside a
+    layer the pool is split equally, the remainder going to the most important caches first:
+    302 = 3 * 100 + 2 with importances [0.3, 0.9, 0.5] gives [100, 101, 101].  No importance lies
+    below t = 0, so Algorithm 2 changes nothing."""
+    got = O.alloc_two_level([1.0, 1000.0], np.array([[0.4, 0.4, 0.4], [0.3, 0.9, 0.5]]), 332, 10, 1000, 0.0, 0.5)
+    assert got == [10, 10, 10, 100, 101, 101]

@@ -8,6 +8,8 @@ namespace {
 
 constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelUnroll = 8;  // score loads in flight per thread in the counting passes
+constexpr int kSelRows = 4;    // consecutive rows per thread in the emit pass
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key); -0 is folded onto +0 so
 // that it ties with it, as a floating-point comparison would.
@@ -75,19 +77,33 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
     for (int shift = 24; shift >= 0; shift -= 8) {
       for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
       __syncthreads();
-      for (int j = mid_lo + tid; j < mid_hi; j += kSelThreads) {
-        const uint32_t key = score_key(score[j]);
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+      // kSelUnroll independent loads per thread before the first use
+      for (int j0 = mid_lo + tid; j0 < mid_hi; j0 += kSelThreads * kSelUnroll) {
+        uint32_t key[kSelUnroll];
+#pragma unroll
+        for (int u = 0; u < kSelUnroll; ++u) {
+          const int j = j0 + u * kSelThreads;
+          key[u] = score_key(j < mid_hi ? score[j] : 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < kSelUnroll; ++u) {
+          const int j = j0 + u * kSelThreads;
+          const bool live = j < mid_hi && (key[u] & mask) == prefix;
+          const uint32_t digit = (key[u] >> shift) & 255;
+          if (live) atomicAdd(&hist[digit], 1);
+        }
       }
       __syncthreads();
-      if (tid == 0) {
-        int cum = 0, d = 255;
-        for (; d > 0; --d) {
-          if (cum + hist[d] >= need) break;
-          cum += hist[d];
+      // The digit of the need-th largest key: thread t looks at digit 255 - t; `above` = keys with a
+      // larger digit.  Exactly one digit has above < need <= above + its own count.
+      {
+        const int mine = tid < 256 ? hist[255 - tid] : 0;
+        int all;
+        const int above = block_exclusive_scan(mine, sm_scan, all);
+        if (tid < 256 && above < need && above + mine >= need) {
+          sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+          sh_need = need - above;
         }
-        sh_prefix = prefix | ((uint32_t)d << shift);
-        sh_need = need - cum;
       }
       __syncthreads();
       prefix = sh_prefix;
@@ -99,26 +115,48 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
     need_eq = need;  // rows whose key equals thr that still survive (oldest first)
   }
 
+  // Stable emit, kSelRows consecutive rows per thread and tile.  A row survives if it is a sink or
+  // recent row, if its key exceeds the threshold, or if it is among the first need_eq rows whose key
+  // equals it; its place in the list is the number of survivors before it, i.e. (rows of the first
+  // two kinds before it) + min(rows with an equal key before it, need_eq).  Both counts come from
+  // one workgroup scan of a packed pair (at most kSelRows * kSelThreads < 2^16 per tile).
   if (tid == 0) sh_first = n;
   __syncthreads();
-  int eq_base = 0, out_base = 0;
-  for (int j0 = 0; j0 < n; j0 += kSelThreads) {
-    const int j = j0 + tid;
-    const bool in = j < n;
-    const bool fixed = in && (j < mid_lo || j >= mid_hi);
-    uint32_t key = 0;
-    const bool middle = in && !fixed;
-    if (middle && k > 0) key = score_key(score[j]);
-    const int is_eq = (middle && k > 0 && key == thr) ? 1 : 0;
-    int eq_total;
-    const int eq_rank = eq_base + block_exclusive_scan(is_eq, sm_scan, eq_total);
-    eq_base += eq_total;
-    const bool keep = fixed || (middle && k > 0 && (key > thr || (is_eq && eq_rank < need_eq)));
-    int keep_total;
-    const int dst = out_base + block_exclusive_scan(keep ? 1 : 0, sm_scan, keep_total);
-    out_base += keep_total;
-    if (keep) kept[dst] = j;
-    else if (in) atomicMin(&sh_first, j);
+  int sure_base = 0, eq_base = 0;
+  for (int j0 = 0; j0 < n; j0 += kSelThreads * kSelRows) {
+    const int jt = j0 + tid * kSelRows;
+    uint32_t key[kSelRows];
+    bool sure[kSelRows], eq[kSelRows];
+    int n_sure = 0, n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < kSelRows; ++i) {
+      const int j = jt + i;
+      const bool in = j < n;
+      const bool middle = in && j >= mid_lo && j < mid_hi;
+      key[i] = (middle && k > 0) ? score_key(score[j]) : 0u;
+      sure[i] = (in && !middle) || (middle && k > 0 && key[i] > thr);
+      eq[i] = middle && k > 0 && key[i] == thr;
+      n_sure += sure[i] ? 1 : 0;
+      n_eq += eq[i] ? 1 : 0;
+    }
+    int total;
+    const int excl = block_exclusive_scan(n_sure | (n_eq << 16), sm_scan, total);
+    int sure_before = sure_base + (excl & 0xffff);
+    int eq_before = eq_base + (excl >> 16);
+    int first_out = n;
+#pragma unroll
+    for (int i = 0; i < kSelRows; ++i) {
+      const int j = jt + i;
+      const bool keep = sure[i] || (eq[i] && eq_before < need_eq);
+      if (keep) kept[sure_before + min(eq_before, need_eq)] = j;
+      else if (j < n) first_out = min(first_out, j);
+      sure_before += sure[i] ? 1 : 0;
+      eq_before += eq[i] ? 1 : 0;
+    }
+    // rows leave in ascending order of the tiles, so only the first tile that evicts has to report
+    if (first_out < n && first_out < *(volatile int*)&sh_first) atomicMin(&sh_first, first_out);
+    sure_base += total & 0xffff;
+    eq_base += total >> 16;
   }
   __syncthreads();
   if (tid == 0) p.info[c] = CompactInfo{b, sh_first, n, 0};

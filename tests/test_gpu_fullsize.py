@@ -87,3 +87,104 @@ def test_full_size_decode_and_compaction(name):
     arena.close()
     del arena
     torch.cuda.empty_cache()
+
+
+def test_cache_longer_than_the_longest_work_item():
+    """A cache of 2^22 + 299 live rows (2.1 GB of K and V): a work item never spans more than 2^22
+    rows, so even a target of one item per launch cuts this cache in two.  Attention in three
+    schedules (two items, one wave of items, the whole-model schedule), the score update over all
+    rows and one eviction are checked against the oracle on the full cache; a second, small layer
+    keeps the launch over layer 0 a layer-range launch."""
+    H = _h()
+    big = (1 << 22) + 100
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="maxrun", L=2, Hq=4, Hkv=1, batch=1, seed=91, sink=4, recent=64,
+                     slack=200)
+    budgets = [big, 100]
+    arena = H.make_arena(w, budgets, track=True)
+    dev = arena.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    n0 = [big + 199, 250]                                  # one append still fits
+    for c in range(2):
+        o, n = int(arena.off_host[c]), n0[c]
+        for a in range(0, n, 1 << 20):                     # in pieces: the fp32 draw of a piece stays small
+            e = min(n, a + (1 << 20))
+            arena.k[o + a:o + e].copy_(torch.randn((e - a, w.D), generator=gen, device=dev).to(torch.bfloat16))
+            arena.v[o + a:o + e].copy_(torch.randn((e - a, w.D), generator=gen, device=dev).to(torch.bfloat16))
+        arena.score[o:o + n].copy_(torch.rand((n,), generator=gen, device=dev))
+        arena.pos[o:o + n].copy_(torch.arange(n, dtype=torch.int32, device=dev))
+    arena.set_lengths(np.asarray(n0, dtype=np.int32))
+    q = torch.randn((2, 1, w.Hq, w.D), generator=gen, device=dev).to(torch.bfloat16)
+    q64 = synth.storage_to_f64(H.from_device_storage(q, "bf16"), "bf16")
+    pre = H.download(arena, w)
+    K64 = [synth.storage_to_f64(pre.K[c], "bf16") for c in range(2)]
+    V64 = [synth.storage_to_f64(pre.V[c], "bf16") for c in range(2)]
+    ref = [O.decode_attn(q64[c, 0], K64[c], V64[c])[0] for c in range(2)]
+    print("maxrun: oracle attention over the stored caches done", flush=True)
+
+    def decode(layer_begin, layer_count):
+        out = torch.full((layer_count, 1, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+        arena.decode_attn(layer_begin, layer_count, q[layer_begin:layer_begin + layer_count], out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy().astype(np.float64)
+
+    # layer-range launch, default target (one wave of work items) and a target of one item (run clamped to 2^22 rows)
+    for target in (None, 1):
+        if target is not None:
+            arena.set_option(B.OPT_TARGET_ITEMS, target)
+            arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
+        o0 = decode(0, 1)
+        err = float(np.max(np.abs(o0[0, 0] - ref[0])))
+        assert err <= H.ATTN_TOL, f"layer-range launch, target {target}: {err:.3e}"
+        ow = decode(0, 2)
+        for c in range(2):
+            err = float(np.max(np.abs(ow[c, 0] - ref[c])))
+            assert err <= H.ATTN_TOL, f"whole-model launch, target {target}, cache {c}: {err:.3e}"
+    n_items = B.plan_schedule(arena.off_host, arena.cap_host, 2, 1, 512, False, target_items=1)
+    runs = [it[2] for it in n_items if it[0] == 0]
+    assert len(runs) == 2 and max(runs) <= 1 << 22 and sum(runs) == big + 200   # the clamp: two runs, not one
+
+    # one fused step (still two items): append, attention, score update over every row; the attention
+    # calls above have added to the scores, so the step starts from the scores as they are now
+    torch.cuda.synchronize()
+    for c in range(2):
+        o = int(arena.off_host[c])
+        pre.score[c] = arena.score[o:o + n0[c]].cpu().numpy()
+    knew = torch.randn((2, 1, 1, w.D), generator=gen, device=dev).to(torch.bfloat16)
+    vnew = torch.randn((2, 1, 1, w.D), generator=gen, device=dev).to(torch.bfloat16)
+    outd = torch.full((2, 1, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+    for l in range(2):
+        arena.append_decode_attn(l, 1, knew[l], vnew[l], 777, q[l], outd[l])
+    torch.cuda.synchronize()
+    out = outd.cpu().numpy().astype(np.float64)
+    post = H.download(arena, w)
+    kn64 = synth.storage_to_f64(H.from_device_storage(knew, "bf16"), "bf16")
+    vn64 = synth.storage_to_f64(H.from_device_storage(vnew, "bf16"), "bf16")
+    for c in range(2):
+        oc = O.Cache(w.D)
+        oc.load(K64[c], V64[c], pre.score[c].astype(np.float64), pre.pos[c])
+        r, _, _ = O.decode_step(oc, q64[c, 0], kn64[c, 0, 0], vn64[c, 0, 0], 777, 1, budget=0, sink=0, recent=0,
+                                interval=0, track_scores=True)
+        assert post.K[c].shape[0] == n0[c] + 1 and post.pos[c][-1] == 777
+        assert float(np.max(np.abs(out[c, 0] - r))) <= H.ATTN_TOL
+        serr = np.abs(post.score[c].astype(np.float64) - oc.score)
+        assert np.all((serr <= 2e-3) | (serr <= 2e-3 * np.abs(oc.score))), f"cache {c}: scores"
+    del K64, V64
+    print("maxrun: fused step checked", flush=True)
+
+    # eviction of the 200 + 151 rows above the budgets, lists and moved rows bit-exact
+    kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev)
+    arena.compact(0, 2, kept_dev)
+    torch.cuda.synchronize()
+    after = H.download(arena, w)
+    for c in range(2):
+        kept = O.compact_select(post.score[c], post.K[c].shape[0], budgets[c], w.sink, w.recent)
+        o = int(arena.off_host[c])
+        assert np.array_equal(kept_dev[o:o + len(kept)].cpu().numpy(), np.asarray(kept, dtype=np.int32)), f"cache {c}"
+        assert after.K[c].shape[0] == budgets[c]
+        idx = np.asarray(kept)
+        assert np.array_equal(after.K[c], post.K[c][idx]) and np.array_equal(after.V[c], post.V[c][idx])
+        assert np.array_equal(after.score[c].view(np.uint32), post.score[c][idx].view(np.uint32))
+        assert np.array_equal(after.pos[c], post.pos[c][idx])
+    assert arena.lengths().tolist() == budgets
+    arena.close()

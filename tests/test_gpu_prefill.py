@@ -179,3 +179,58 @@ def test_full_size_prompt_scores_and_large_ratio_eviction():
     run_compact_and_check(arena, w, st)
     assert arena.lengths().tolist() == budgets
     arena.close()
+
+
+def test_longest_context_prompt_through_both_prompt_kernels():
+    """A prompt of 131072 tokens (the longest context any workload names), 4 query heads on 2 KV
+    heads: the profiling kernel's per-token cosines on the first 1024 tokens (oracle, token by token)
+    and on sampled late tokens (Eq. 1 row by row through the oracle's attention), its log-sum-exp
+    on the same tokens, then the prompt-wide scores: total mass G*T per cache and the last 64
+    columns against their definition."""
+    H = _h()
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(515)
+    Hq, Hkv, T, D = 4, 2, 131072, 128
+    G = Hq // Hkv
+    q = torch.randn((1, Hq, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn((1, Hkv, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((1, Hkv, T, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sim, cos, lse = B.profile_similarity(q, k, v, want_cos=True, want_lse=True)
+    score = torch.full((Hkv * T,), float("nan"), dtype=torch.float32, device=dev)
+    B.prefill_scores(q, k, lse, score, 1, Hq, Hkv, T)
+    torch.cuda.synchronize()
+    cos_h = cos.cpu().numpy().astype(np.float64)
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(cos_h)) and np.all(np.abs(cos_h) <= 1.0 + 1e-5)
+    assert np.allclose(sim.cpu().numpy()[0], cos_h[0].mean(axis=1), rtol=0, atol=1e-5)
+    head = 3
+    q64 = synth.storage_to_f64(H.from_device_storage(q[0, head], "bf16"), "bf16")
+    k64 = synth.storage_to_f64(H.from_device_storage(k[0, head // G], "bf16"), "bf16")
+    v64 = synth.storage_to_f64(H.from_device_storage(v[0, head // G], "bf16"), "bf16")
+    # the first tokens depend on nothing later: the oracle on the prefix is the oracle on the prompt
+    _, want = O.head_similarity(q64[:1024], k64[:1024], v64[:1024])
+    assert np.max(np.abs(cos_h[0, head, :1024] - want)) <= 1e-4
+    assert np.max(np.abs(lse_h[0, head, :1024] - oracle_lse2(q64[:1024], k64[:1024]))) <= LSE_TOL
+    for t in (1024, 65535, 65536, 100000, T - 129, T - 128, T - 2, T - 1):
+        out, _ = O.decode_attn(q64[t][None, :], k64[: t + 1], v64[: t + 1])     # Eq. 1 for token t alone
+        c = float(v64[t] @ out[0]) / max(float(np.linalg.norm(v64[t]) * np.linalg.norm(out[0])), O.COS_EPS)
+        assert abs(cos_h[0, head, t] - c) <= 1e-4, f"token {t}"
+        s = (k64[: t + 1] @ q64[t]) / np.sqrt(D) * np.log2(np.e)
+        assert abs(lse_h[0, head, t] - (s.max() + np.log2(np.sum(np.exp2(s - s.max()))))) <= LSE_TOL, f"token {t}"
+    got = score.cpu().numpy().astype(np.float64).reshape(Hkv, T)
+    assert np.all(np.isfinite(got)) and np.all(got >= 0)
+    tail = 64
+    for c in range(Hkv):
+        assert abs(got[c].sum() - G * T) <= 1e-4 * G * T
+    qt = synth.storage_to_f64(H.from_device_storage(q[0, G:2 * G, T - tail:], "bf16"), "bf16")   # heads of KV head 1
+    want = np.zeros(tail)
+    for g in range(G):
+        for i in range(tail):
+            t = T - tail + i
+            s = (k64[: t + 1] @ qt[g, i]) / np.sqrt(D)
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            want[: i + 1] += p[T - tail: t + 1]
+    err = np.abs(got[1, -tail:] - want) / np.maximum(1.0, want)
+    assert err.max() <= SCORE_RTOL, f"{err.max():.3e}"

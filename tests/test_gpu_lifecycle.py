@@ -92,3 +92,57 @@ def test_evict_every_step(policy):
                      seed=62, sink=3, recent=0 if policy == B.POLICY_STREAMING else 5, interval=1, slack=1)
     budgets = [12, 45, 30, 8]
     run_from_empty(w, budgets, policy, steps=60, chunks=[256])
+
+
+def test_two_contexts_used_alternately():
+    """Two arenas of different shapes on one device, their calls interleaved on the same stream: a
+    context keeps all of its state in its own workspace, so neither disturbs the other."""
+    H = _h()
+    wa = synth.shrink(synth.WORKLOADS["long"], name="ctxA", L=2, Hq=8, Hkv=2, D=128, batch=2, dtype="bf16", seed=71,
+                      sink=2, recent=4, slack=16, interval=4)
+    wb = synth.shrink(synth.WORKLOADS["long"], name="ctxB", L=1, Hq=7, Hkv=1, D=128, batch=3, dtype="bf16", seed=72,
+                      sink=1, recent=2, slack=16, interval=4)
+    ba, bb = [700, 90, 300, 1500], [400]
+    ra, rb = np.random.Generator(np.random.PCG64(71)), np.random.Generator(np.random.PCG64(72))
+    A, Bn = H.make_arena(wa, ba, track=True), H.make_arena(wb, bb, track=True)
+    cpl_a = wa.batch * wa.Hkv
+    sta = H.fill_from_host(A, wa, [ba[(c // cpl_a) * wa.Hkv + c % wa.Hkv] for c in range(A.n_caches)], ra, scores="zero")
+    stb = H.fill_from_host(Bn, wb, [bb[0]] * Bn.n_caches, rb, scores="zero")
+    for t in range(1, 6):
+        calls = []
+        for arena, w, r in ((A, wa, ra), (Bn, wb, rb)):
+            q, q64 = H.make_q(w, r, w.L)
+            knew, vnew = synth.payload(r, (w.L, w.batch, w.Hkv, w.D), "bf16"), synth.payload(r, (w.L, w.batch, w.Hkv, w.D), "bf16")
+            outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=arena.device)
+            calls.append((arena, w, H.download(arena, w), q64, knew, vnew, outd,
+                          H.to_device_storage(q, "bf16", arena.device), H.to_device_storage(knew, "bf16", arena.device),
+                          H.to_device_storage(vnew, "bf16", arena.device)))
+        # layer by layer, the two contexts taking turns, no synchronisation in between
+        for l in range(2):
+            for arena, w, _, _, _, _, outd, qd, kd, vd in calls:
+                if l < w.L:
+                    arena.append_decode_attn(l, 1, kd[l], vd[l], 900 + t, qd[l], outd[l])
+        if t % 4 == 0:
+            A.compact(0, wa.L)
+            Bn.compact(0, wb.L)
+        torch.cuda.synchronize()
+        for arena, w, pre, q64, knew, vnew, outd, _, _, _ in calls:
+            out = outd.cpu().numpy().astype(np.float64)
+            k64, v64 = synth.storage_to_f64(knew, "bf16"), synth.storage_to_f64(vnew, "bf16")
+            budgets = ba if arena is A else bb
+            cpl = w.batch * w.Hkv
+            post = H.download(arena, w)
+            for c in range(arena.n_caches):
+                l, b, hs = H.q_rows_of_cache(w, c)
+                h = c % w.Hkv
+                oc = H.oracle_cache(w, pre, c)
+                ref, _, _ = O.decode_step(oc, q64[l, b, hs], k64[l, b, h], v64[l, b, h], 900 + t, t, 0, 0, 0, 0, True)
+                assert np.max(np.abs(out[l, b, hs] - ref)) <= H.ATTN_TOL, f"step {t} cache {c}"
+                if t % 4 == 0:
+                    # selection judged on fp32 scores within tolerance of the oracle's: lengths only here
+                    assert post.K[c].shape[0] == min(oc.n, budgets[(c // cpl) * w.Hkv + c % w.Hkv])
+                else:
+                    serr = np.abs(post.score[c].astype(np.float64) - oc.score)
+                    assert np.all((serr <= 2e-3) | (serr <= 2e-3 * np.abs(oc.score)))
+    A.close()
+    Bn.close()

@@ -381,6 +381,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       return BAKLAVA_EHIP;
     }
   }
+  if (!hip_ok(prepare_decode_mfma())) { delete ctx; return BAKLAVA_EHIP; }
   int st = build_schedule(ctx, 0, kDefaultChunk);
   if (st == BAKLAVA_OK) st = build_schedule(ctx, 1, kDefaultChunkWhole);
   if (st != BAKLAVA_OK) { delete ctx; return st; }

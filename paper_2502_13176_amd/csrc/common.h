@@ -131,6 +131,7 @@ hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_ite
 // max_count: longest work item of the launch (rows); one_wave: the launch has at most one workgroup per
 // compute unit, so a workgroup may take the whole LDS (score tracking keeps its logits there)
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, int max_count, bool one_wave, hipStream_t s);
+hipError_t prepare_decode_mfma();
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
                                      int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
                                      hipStream_t s);

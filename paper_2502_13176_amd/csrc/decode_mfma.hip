@@ -320,6 +320,18 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
 
 }  // namespace
 
+// Dynamic LDS the attention kernel may ask for: the whole LDS of a CU minus the static staging areas.
+constexpr int kLdsTotal = 160 * 1024;
+constexpr int kStatic = kWaves * kSlab * (kVStride + kKStride);
+constexpr int kDynMax = kLdsTotal - kStatic - 512;
+
+// Called when a context is created on the current device, i.e. outside any stream capture: raises
+// the kernel's dynamic-LDS limit once, so that launches (captured or not) only launch.
+hipError_t prepare_decode_mfma() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kDynMax);
+}
+
 hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_count, bool one_wave, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
   if (p_in.G > 16) return hipErrorInvalidValue;
@@ -327,21 +339,12 @@ hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_cou
   p.stash_slots = 0;
   size_t dyn = 0;
   if (p.track && one_wave) {
-    // the whole LDS of a CU minus the static staging areas, split over the wavefronts
-    constexpr int kLdsTotal = 160 * 1024;
-    constexpr int kStatic = kWaves * kSlab * (kVStride + kKStride);
+    // the LDS left beside the staging areas, split over the wavefronts
     const int slot_bytes = kSlab * p.G * 4;
-    const int fit = (kLdsTotal - kStatic - 512) / (kWaves * slot_bytes);
+    const int fit = kDynMax / (kWaves * slot_bytes);
     const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;  // slabs of the longest item per wavefront
     p.stash_slots = std::max(1, std::min(fit, need));
     dyn = (size_t)p.stash_slots * kWaves * slot_bytes;
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTotal - kStatic - 512);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
   }
   decode_partial_mfma<<<dim3(n_items), dim3(64 * kWaves), dyn, s>>>(p);
   return hipGetLastError();

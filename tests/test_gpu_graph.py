@@ -15,8 +15,10 @@ def _h():
     return gpu_harness
 
 
-@pytest.mark.parametrize("track", [False, True])
-def test_decode_step_replays_from_a_graph(track):
+@pytest.mark.parametrize("track,warm", [(False, True), (True, True), (True, False)])
+def test_decode_step_replays_from_a_graph(track, warm):
+    """warm = False: the capture holds the context's very first launches (everything a launch needs
+    beyond the launch itself was set up when the context was created)."""
     H = _h()
     w = synth.shrink(synth.WORKLOADS["llama32"], name="graph", L=3, Hq=8, Hkv=2, batch=2, seed=51, slack=64)
     rng = np.random.Generator(np.random.PCG64(w.seed))
@@ -33,11 +35,12 @@ def test_decode_step_replays_from_a_graph(track):
         for l in range(w.L):                       # one launch per layer, as a model issues them
             arena.decode_attn(l, 1, q_static[l], out_static[l])
 
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        step()                                     # warm-up outside the capture
-    torch.cuda.current_stream().wait_stream(side)
+    if warm:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                 # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     arena.score.zero_()                            # the warm-up accumulated scores when tracking is on
     graph = torch.cuda.CUDAGraph()

@@ -177,7 +177,9 @@ enum {
   BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* the same for launches over all layers at once               */
   BAKLAVA_OPT_TARGET_ITEMS = 5, /* > 0: launches over part of the layers lengthen their runs, layer by
                                    layer, until a layer has at most this many work items; 0: off.
-                                   Default: the device's number of compute units                    */
+                                   Default: the device's number of compute units (one wave of
+                                   workgroups) while a layer holds at most a quarter as many caches,
+                                   otherwise five times that number, with a shortest run of 256 rows */
   BAKLAVA_OPT_TARGET_ITEMS_WHOLE = 6 /* the same for launches over all layers at once.  Default: five
                                    times the device's number of compute units                      */
 };

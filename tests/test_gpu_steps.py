@@ -24,29 +24,33 @@ def _h():
 
 
 # the vector-ALU kernel serves at most 8 query heads per KV head
-STEP_CASES = [(kernel, fused, base, Hq, Hkv, target)
+STEP_CASES = [(kernel, fused, base, Hq, Hkv, target, 2)
               for base, Hq, Hkv, target in [("long", 8, 2, 0), ("qwen", 7, 1, 0), ("long", 8, 2, 3), ("long", 16, 1, 1)]
               for fused in (False, True)
               for kernel in (B.KERNEL_VALU, B.KERNEL_MFMA)
               if not (kernel == B.KERNEL_VALU and Hq // Hkv > 8)]
+# 9 sequences x 8 KV heads = 72 caches per layer: more than a quarter of the compute units, so the
+# library's own defaults (target -1: nothing is set here) give layer launches several waves of work items
+STEP_CASES += [(B.KERNEL_MFMA, True, "long", 16, 8, -1, 9), (B.KERNEL_MFMA, False, "long", 16, 8, -1, 9)]
 
 
-@pytest.mark.parametrize("kernel,fused,base,Hq,Hkv,target", STEP_CASES)
-def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv, target):
+@pytest.mark.parametrize("kernel,fused,base,Hq,Hkv,target,batch", STEP_CASES)
+def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv, target, batch):
     H = _h()
-    w = synth.shrink(synth.WORKLOADS[base], name="steps", L=2, Hq=Hq, Hkv=Hkv, batch=2, ctx=2048, lo=96,
-                     hi=2048, interval=8, slack=8, sink=4, recent=16, steps=20, floor_frac=0.0)
+    w = synth.shrink(synth.WORKLOADS[base], name="steps", L=2, Hq=Hq, Hkv=Hkv, batch=batch, ctx=2048, lo=96,
+                     hi=2048, interval=8, slack=8, sink=4, recent=16, steps=20 if batch == 2 else 9, floor_frac=0.0)
     rng = np.random.Generator(np.random.PCG64(w.seed))
     budgets = synth.budgets_for(w, B.alloc_proportional)
     assert budgets == synth.budgets_for(w, O.alloc_proportional)
     arena = H.make_arena(w, budgets, track=True)
     arena.set_option(B.OPT_KERNEL, kernel)
-    H.set_chunk(arena, 256)
-    # target 3: at most 3 work items per layer launch, so work items of up to 2048 rows whose score
-    # update spans several workgroups; 16 query heads per KV head with one item per cache: more logits
-    # than the attention kernel can hold on chip, so it writes them out in several batches
-    arena.set_option(B.OPT_TARGET_ITEMS, target)
-    arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
+    if target >= 0:
+        H.set_chunk(arena, 256)
+        # target 3: at most 3 work items per layer launch, so work items of up to 2048 rows whose score
+        # update spans several workgroups; 16 query heads per KV head with one item per cache: more logits
+        # than the attention kernel can hold on chip, so it writes them out in several batches
+        arena.set_option(B.OPT_TARGET_ITEMS, target)
+        arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
     cpl = w.batch * w.Hkv
     lens = [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]
     H.fill_from_host(arena, w, lens, rng, scores="zero")

@@ -148,3 +148,42 @@ def set_chunk(arena: B.Arena, chunk: int) -> None:
     """Rows per split-K work item, for both kinds of launch (layer sub-range and whole model)."""
     arena.set_option(B.OPT_CHUNK_TOKENS, chunk)
     arena.set_option(B.OPT_CHUNK_TOKENS_WHOLE, chunk)
+
+
+def check_step_against_oracle(arena, w, pre: HostState, post: HostState, out: np.ndarray, q64: np.ndarray,
+                              k64: np.ndarray, v64: np.ndarray, token_pos: int, t: int, caches: Sequence[int],
+                              score_tol: float = 2e-3):
+    """Step-local check of one decode step (append, attention, score update) on the given caches: the
+    oracle starts from the device's own pre-step state, recomputes the step in fp64, and the device's
+    outputs, appended rows and post-step scores must agree.  Returns (worst output error, worst score error)."""
+    worst_out = worst_score = 0.0
+    for c in caches:
+        l, b, hs = q_rows_of_cache(w, c)
+        h = c % w.Hkv
+        oc = oracle_cache(w, pre, c)
+        ref, _, _ = O.decode_step(oc, q64[l, b, hs], k64[l, b, h], v64[l, b, h], token_pos, t,
+                                  budget=0, sink=0, recent=0, interval=0, track_scores=True)
+        assert post.K[c].shape[0] == pre.K[c].shape[0] + 1 and post.pos[c][-1] == token_pos, f"step {t} cache {c}"
+        err = float(np.max(np.abs(out[l, b, hs] - ref)))
+        assert err <= ATTN_TOL, f"step {t} cache {c}: attention error {err:.3e}"
+        serr = np.abs(post.score[c].astype(np.float64) - oc.score)
+        assert np.all((serr <= score_tol) | (serr <= score_tol * np.abs(oc.score))), \
+            f"step {t} cache {c}: score error {serr.max():.3e}"
+        worst_out, worst_score = max(worst_out, err), max(worst_score, float(serr.max()))
+    return worst_out, worst_score
+
+
+def check_eviction_against_oracle(arena, w, budgets, post: HostState, after: HostState, kept_dev, caches: Sequence[int]):
+    """The oracle's selection on the device's own fp32 post-step scores must give the device's kept
+    list, and the surviving rows must be the selected ones, bit for bit."""
+    cpl = w.batch * w.Hkv
+    for c in caches:
+        bud = budgets[(c // cpl) * w.Hkv + c % w.Hkv]
+        kept = O.compact_select(post.score[c], post.K[c].shape[0], bud, w.sink, w.recent)
+        o = int(arena.off_host[c])
+        assert np.array_equal(kept_dev[o:o + len(kept)].cpu().numpy(), np.asarray(kept, dtype=np.int32)), f"cache {c}: kept list"
+        idx = np.asarray(kept)
+        assert after.K[c].shape[0] == len(kept) == min(post.K[c].shape[0], bud)
+        assert np.array_equal(after.K[c], post.K[c][idx]) and np.array_equal(after.V[c], post.V[c][idx])
+        assert np.array_equal(after.score[c].view(np.uint32), post.score[c][idx].view(np.uint32))
+        assert np.array_equal(after.pos[c], post.pos[c][idx])

@@ -188,3 +188,57 @@ def test_cache_longer_than_the_longest_work_item():
         assert np.array_equal(after.pos[c], post.pos[c][idx])
     assert arena.lengths().tolist() == budgets
     arena.close()
+
+
+def test_long_workload_trajectory_at_full_size():
+    """The long workload as bench.py runs it (1024 caches of up to 131072 rows, one fused launch per
+    layer, scores from the kernel, eviction every 32 steps), all 256 steps at full size; steps 1, 32,
+    33 and 256 are checked step-locally on sampled caches (the longest and the shortest among them),
+    the evictions after steps 32 and 256 bit for bit on the same caches; lengths on all caches."""
+    H = _h()
+    w = synth.WORKLOADS["long"]
+    rng = np.random.Generator(np.random.PCG64(w.seed + 11))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    arena = H.make_arena(w, budgets, track=True)
+    gen = synth.fill_arena_on_device(arena, w)
+    cpl = w.batch * w.Hkv
+    bud_of = np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], dtype=np.int32)
+    arena.set_lengths(bud_of)
+    arena.score.zero_()
+    dev = arena.device
+    picks = sample_caches(arena, bud_of, rng, n_random=6)
+    checked = (1, 32, 33, 256)
+    shape_q, shape_kv = (w.L, w.batch, w.Hq, w.D), (w.L, w.batch, w.Hkv, w.D)
+    out = torch.zeros(shape_q, dtype=torch.float32, device=dev)
+    for t in range(1, w.steps + 1):
+        q = torch.randn(shape_q, generator=gen, device=dev).to(torch.bfloat16)
+        kn = torch.randn(shape_kv, generator=gen, device=dev).to(torch.bfloat16)
+        vn = torch.randn(shape_kv, generator=gen, device=dev).to(torch.bfloat16)
+        pre = H.download(arena, w, picks) if t in checked else None
+        for l in range(w.L):
+            arena.append_decode_attn(l, 1, kn[l], vn[l], w.ctx + t, q[l], out[l])
+        post = None
+        if t in checked:
+            post = H.download(arena, w, picks)
+            q64 = synth.storage_to_f64(H.from_device_storage(q, "bf16"), "bf16")
+            e = H.check_step_against_oracle(arena, w, pre, post, out.cpu().numpy().astype(np.float64), q64,
+                                            synth.storage_to_f64(H.from_device_storage(kn, "bf16"), "bf16"),
+                                            synth.storage_to_f64(H.from_device_storage(vn, "bf16"), "bf16"),
+                                            w.ctx + t, t, picks)
+            print(f"long, step {t}: {len(picks)} sampled caches, worst attention error {e[0]:.3e}, "
+                  f"worst score error {e[1]:.3e}", flush=True)
+        if t % w.interval == 0:
+            kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev) if post is not None else None
+            arena.compact(0, w.L, kept_dev)
+            if post is not None:
+                torch.cuda.synchronize()
+                H.check_eviction_against_oracle(arena, w, budgets, post, H.download(arena, w, picks), kept_dev, picks)
+            assert np.array_equal(arena.lengths(), bud_of)
+        else:
+            assert np.array_equal(arena.lengths(), bud_of + t % w.interval)
+    torch.cuda.synchronize()
+    assert np.array_equal(arena.len.cpu().numpy(), bud_of)
+    assert bool(torch.isfinite(arena.score).all())
+    arena.close()
+    del arena
+    torch.cuda.empty_cache()

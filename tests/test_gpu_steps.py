@@ -194,3 +194,43 @@ def test_free_running_fp64_oracle_on_a_small_replica():
                     diverged[c] = True
     print(f"free-running oracle: {inside_margin} of {arena.n_caches} caches fell inside the score margin", flush=True)
     arena.close()
+
+
+def test_256_step_trajectory_on_a_small_replica_of_the_long_workload():
+    """The long workload's whole trajectory (256 steps, eviction every 32, scores from the kernel's
+    softmax weights) on a replica with 2 layers, one sequence and an 8192-token context: every step
+    is checked step-locally on every cache, every eviction bit for bit."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["long"], name="traj", L=2, batch=1, ctx=8192, lo=256, hi=8192)
+    assert w.interval == 32 and w.steps == 256 and w.scores == "kernel"
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    assert budgets == synth.budgets_for(w, O.alloc_proportional)
+    arena = H.make_arena(w, budgets, track=True)
+    cpl = w.batch * w.Hkv
+    H.fill_from_host(arena, w, [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], rng, scores="zero")
+    dev = arena.device
+    every = range(arena.n_caches)
+    worst = (0.0, 0.0)
+    for t in range(1, w.steps + 1):
+        pre = H.download(arena, w)
+        q, q64 = H.make_q(w, rng, w.L)
+        knew, vnew = synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype), synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype)
+        kd, vd, qd = (H.to_device_storage(a, w.dtype, dev) for a in (knew, vnew, q))
+        outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+        for l in range(w.L):
+            arena.append_decode_attn(l, 1, kd[l], vd[l], w.ctx + t, qd[l], outd[l])
+        torch.cuda.synchronize()
+        post = H.download(arena, w)
+        e = H.check_step_against_oracle(arena, w, pre, post, outd.cpu().numpy().astype(np.float64), q64,
+                                        synth.storage_to_f64(knew, w.dtype), synth.storage_to_f64(vnew, w.dtype),
+                                        w.ctx + t, t, every)
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        if t % w.interval == 0:
+            kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev)
+            arena.compact(0, w.L, kept_dev)
+            torch.cuda.synchronize()
+            H.check_eviction_against_oracle(arena, w, budgets, post, H.download(arena, w), kept_dev, every)
+        assert arena.lengths().tolist() == arena.len.cpu().tolist()
+    print(f"256-step replica: worst attention error {worst[0]:.3e}, worst score error {worst[1]:.3e}", flush=True)
+    arena.close()

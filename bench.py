@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-track", action="store_true", help="do not accumulate attention scores (long workload)")
     ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
+    ap.add_argument("--keep-pct", type=int, default=0,
+                    help="percent of the context kept globally instead of the workload's own (the other reading of "
+                         "'compression X%%': X%% kept rather than X%% evicted)")
     ap.add_argument("--interval", type=int, default=0,
                     help="evict every N steps instead of the workload's own interval (capacity = budget + N)")
     ap.add_argument("--policy", default="score", choices=["score", "streaming"],
@@ -342,6 +345,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.interval > 0:
         w = synth.shrink(w, interval=args.interval, slack=args.interval)
+    if args.keep_pct > 0:
+        w = synth.shrink(w, keep_pct=args.keep_pct)
     budgets = synth.budgets_for(w, B.alloc_proportional)
     track = w.scores == "kernel" and not args.no_track
     policy = B.POLICY_STREAMING if args.policy == "streaming" else B.POLICY_SCORE

@@ -70,6 +70,12 @@ def cpu_baseline(arena, w, q_dev, torch, target_seconds):
     q_host = q_dev.view(torch.int16).cpu().numpy().view(np.uint16) if w.dtype == "bf16" else q_dev.cpu().numpy()
     q64 = synth.storage_to_f64(q_host, w.dtype)
     cpl = w.batch * w.Hkv
+    # the library's answer on the same state, for the error of the sampled caches
+    out_dev = torch.zeros((w.L, w.batch, w.Hq, w.D), dtype=torch.float32, device=arena.device)
+    arena.decode_attn(0, w.L, q_dev, out_dev)
+    torch.cuda.synchronize()
+    out_host = out_dev.cpu().numpy().astype(np.float64)
+    worst = 0.0
     t_used, bytes_done, n_done = 0.0, 0, 0
     for c in range(arena.n_caches):
         o, n = int(arena.off_host[c]), int(lens[c])
@@ -81,9 +87,10 @@ def cpu_baseline(arena, w, q_dev, torch, target_seconds):
         l, rem = divmod(c, cpl)
         b, h = divmod(rem, w.Hkv)
         t0 = time.perf_counter()
-        O.decode_attn(q64[l, b, h * w.G:(h + 1) * w.G], synth.storage_to_f64(Ks, w.dtype),
-                      synth.storage_to_f64(Vs, w.dtype))
+        ref, _ = O.decode_attn(q64[l, b, h * w.G:(h + 1) * w.G], synth.storage_to_f64(Ks, w.dtype),
+                               synth.storage_to_f64(Vs, w.dtype))
         t_used += time.perf_counter() - t0
+        worst = max(worst, float(np.max(np.abs(out_host[l, b, h * w.G:(h + 1) * w.G] - ref))))
         bytes_done += n * w.token_bytes
         n_done += 1
         if t_used >= target_seconds:
@@ -92,6 +99,7 @@ def cpu_baseline(arena, w, q_dev, torch, target_seconds):
         "value": round(bytes_done / t_used / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
         "sample": f"fp64 oracle decode attention over the first {n_done} of {arena.n_caches} caches "
                   f"({bytes_done / 1e6:.1f} MB of K/V, {t_used:.1f} s), widening of the stored rows included",
+        "max_abs_error_vs_oracle_on_sample": worst,
     }
 
 

@@ -74,6 +74,77 @@ int main() {
     CHECK(baklava_layout(bud.data(), 2, 2, 2, 3, off.data(), cap.data(), &total) == BAKLAVA_EINVAL);
     CHECK(baklava_layout(bud.data(), 0, 2, 2, 3, off.data(), cap.data(), &total) == BAKLAVA_EINVAL);
   }
+  // split-K planner: random capacities (zero, tiny, beyond the longest run), every target / launch kind
+  for (int rep = 0; rep < 200; ++rep) {
+    const int L = 1 + (int)(rng() % 4), cpl = 1 + (int)(rng() % 9);
+    const int n = L * cpl;
+    std::vector<int32_t> cap(n);
+    std::vector<int64_t> off(n);
+    int64_t total = 0;
+    for (int c = 0; c < n; ++c) {
+      const uint64_t r = rng() % 100;
+      cap[c] = r < 5 ? 0 : r < 60 ? (int32_t)(rng() % 700) : r < 98 ? (int32_t)(rng() % 200000) : (int32_t)((1 << 22) + rng() % 5000);
+      off[c] = total;
+      total += cap[c];
+    }
+    const int chunk = 256 + 64 * (int)(rng() % 30);
+    const int target = (rng() % 3 == 0) ? 0 : 1 + (int)(rng() % 600);
+    const int whole = (int)(rng() % 2);
+    int64_t n_items = -1;
+    CHECK(baklava_plan_schedule(off.data(), cap.data(), L, cpl, chunk, target, whole, 0, nullptr, &n_items) == BAKLAVA_OK);
+    CHECK(n_items >= n);
+    std::vector<baklava_work_item> items((size_t)n_items);
+    int64_t n2 = -1;
+    CHECK(baklava_plan_schedule(off.data(), cap.data(), L, cpl, chunk, target, whole, n_items, items.data(), &n2) == BAKLAVA_OK);
+    CHECK(n2 == n_items);
+    std::vector<int64_t> rows(n, 0);
+    std::vector<char> slot_seen((size_t)n_items, 0);
+    for (const baklava_work_item& it : items) {
+      CHECK(it.cache >= 0 && it.cache < n && it.count >= 0 && it.count <= (1 << 22));
+      CHECK(it.start % 64 == 0 && it.start + (int64_t)it.count <= cap[it.cache] && it.row0 == off[it.cache] + it.start);
+      CHECK(it.slot >= 0 && it.slot < n_items && !slot_seen[it.slot]);
+      slot_seen[it.slot] = 1;
+      rows[it.cache] += it.count;
+    }
+    for (int c = 0; c < n; ++c) CHECK(rows[c] == cap[c]);
+    if (n_items > 1) {
+      CHECK(baklava_plan_schedule(off.data(), cap.data(), L, cpl, chunk, target, whole, n_items - 1, items.data(), &n2) == BAKLAVA_ECAPACITY);
+      CHECK(n2 == n_items);
+    }
+  }
+  {
+    int64_t off1 = 0, n_items = 0;
+    int32_t cap1 = 1000;
+    CHECK(baklava_plan_schedule(&off1, &cap1, 1, 1, 100, 0, 0, 0, nullptr, &n_items) == BAKLAVA_EINVAL);   // chunk below 256
+    CHECK(baklava_plan_schedule(&off1, &cap1, 1, 1, 300, 0, 0, 0, nullptr, &n_items) == BAKLAVA_EINVAL);   // not a multiple of 64
+    CHECK(baklava_plan_schedule(nullptr, &cap1, 1, 1, 256, 0, 0, 0, nullptr, &n_items) == BAKLAVA_EINVAL);
+    cap1 = -5;
+    CHECK(baklava_plan_schedule(&off1, &cap1, 1, 1, 256, 0, 0, 0, nullptr, &n_items) == BAKLAVA_EINVAL);
+  }
+  // importances from similarities, and the two-level allocation
+  for (int rep = 0; rep < 200; ++rep) {
+    const int L = 1 + (int)(rng() % 6), Hkv = 1 + (int)(rng() % 8), G = 1 + (int)(rng() % 8);
+    std::vector<double> sim((size_t)L * Hkv * G), imp((size_t)L * Hkv), limp(L);
+    for (double& v : sim) v = (double)(rng() % 2001) / 1000.0 - 1.0;
+    CHECK(baklava_kv_importance(sim.data(), L, Hkv * G, Hkv, imp.data()) == BAKLAVA_OK);
+    for (double v : imp) CHECK(v >= 0.0 && v <= 1.0);
+    for (double& v : limp) v = 0.001 + (double)(rng() % 1000) / 1000.0;
+    for (double& v : imp) v += 1e-6;                              // strictly positive for the allocator
+    const int lo = 1 + (int)(rng() % 50), hi = lo + 1 + (int)(rng() % 5000);
+    const int64_t m = (int64_t)L * Hkv;
+    const int64_t B = m * lo + (int64_t)(rng() % (uint64_t)(m * (hi - lo) + 1));
+    std::vector<int32_t> bud((size_t)m, -1);
+    CHECK(baklava_alloc_two_level(limp.data(), imp.data(), L, Hkv, B, lo, hi, 0.5, 0.25, bud.data()) == BAKLAVA_OK);
+    int64_t sum = 0;
+    for (int32_t b : bud) { CHECK(b >= 0); sum += b; }
+    CHECK(sum == B);
+    CHECK(baklava_alloc_two_level(limp.data(), imp.data(), L, Hkv, m * lo - 1, lo, hi, 0.5, 0.25, bud.data()) == BAKLAVA_EINFEASIBLE);
+  }
+  CHECK(baklava_kv_importance(nullptr, 1, 4, 2, nullptr) == BAKLAVA_EINVAL);
+  {
+    double s4[4] = {0.1, 0.2, 0.3, 0.4}, o2[2];
+    CHECK(baklava_kv_importance(s4, 1, 4, 3, o2) == BAKLAVA_EINVAL);   // 4 heads do not split over 3 KV heads
+  }
   CHECK(baklava_strerror(BAKLAVA_OK) != nullptr && baklava_strerror(12345) != nullptr);
   std::printf("%s (%d failures)\n", fails ? "FAILED" : "ok", fails);
   return fails ? 1 : 0;

@@ -197,7 +197,7 @@ class Arena:
 
     def __init__(self, L: int, Hq: int, Hkv: int, D: int, batch: int, dtype: str, budget: Sequence[int],
                  slack: int, sink: int, recent: int, policy: int = POLICY_SCORE, track_scores: bool = False,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", workspace_fill: int = 0):
         import torch
         self.torch = torch
         self.L, self.Hq, self.Hkv, self.D, self.batch = L, Hq, Hkv, D, batch
@@ -226,7 +226,8 @@ class Arena:
                                                  _p(self.budget_host, C.c_int32))
         if ws_bytes == 0:
             raise BaklavaError(EINVAL, "baklava_workspace_bytes")
-        self.workspace = torch.zeros((ws_bytes,), dtype=torch.uint8, device=dev)
+        # the library does not rely on the workspace's initial contents; tests fill it with 0xFF bytes
+        self.workspace = torch.full((ws_bytes,), int(workspace_fill), dtype=torch.uint8, device=dev)
         d.k, d.v = self.k.data_ptr(), self.v.data_ptr()
         d.score, d.pos = self.score.data_ptr(), self.pos.data_ptr()
         d.off, d.cap, d.len, d.budget = (self.off.data_ptr(), self.cap.data_ptr(), self.len.data_ptr(),

@@ -30,8 +30,15 @@ def make_arena(w: synth.Workload, budgets: Optional[Sequence[int]] = None, track
                policy: int = B.POLICY_SCORE, slack: Optional[int] = None) -> B.Arena:
     if budgets is None:
         budgets = synth.budgets_for(w, B.alloc_proportional)
-    return B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack if slack is None else slack,
-                   w.sink, w.recent, policy, track)
+    arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack if slack is None else slack,
+                    w.sink, w.recent, policy, track, workspace_fill=0xFF)
+    # Rows beyond a cache's live length must never reach a result, and the library must not count on
+    # a zeroed workspace: everything starts out as NaN (K, V, scores), -1 (positions) and 0xFF bytes.
+    arena.k.fill_(float("nan"))
+    arena.v.fill_(float("nan"))
+    arena.score.fill_(float("nan"))
+    arena.pos.fill_(-1)
+    return arena
 
 
 class HostState:
@@ -52,10 +59,11 @@ def fill_from_host(arena: B.Arena, w: synth.Workload, lens: Sequence[int], rng: 
     """Seeded payload for every cache, uploaded in one copy per plane.  Small arenas only."""
     st = HostState(arena.n_caches)
     sdt = np.float32 if w.dtype == "f32" else np.uint16
-    Kh = np.zeros((arena.total_tokens, w.D), dtype=sdt)
-    Vh = np.zeros((arena.total_tokens, w.D), dtype=sdt)
-    Sh = np.zeros((arena.total_tokens,), dtype=np.float32)
-    Ph = np.zeros((arena.total_tokens,), dtype=np.int32)
+    nan = np.float32(np.nan) if w.dtype == "f32" else np.uint16(0x7FC0)      # rows past the live length stay NaN
+    Kh = np.full((arena.total_tokens, w.D), nan, dtype=sdt)
+    Vh = np.full((arena.total_tokens, w.D), nan, dtype=sdt)
+    Sh = np.full((arena.total_tokens,), np.nan, dtype=np.float32)
+    Ph = np.full((arena.total_tokens,), -1, dtype=np.int32)
     for c in range(arena.n_caches):
         n = int(lens[c])
         assert n <= arena.cap_host[c]

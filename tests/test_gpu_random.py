@@ -87,6 +87,14 @@ def test_seeded_random_configuration(seed):
             assert err <= H.ATTN_TOL, f"step {t} cache {c}: attention error {err:.3e}"
             serr = np.abs(post.score[c].astype(np.float64) - oc.score)
             assert np.all((serr <= SCORE_TOL) | (serr <= SCORE_TOL * np.abs(oc.score))), f"step {t} cache {c}: scores"
+    # nothing was written beyond the rows the appends filled: the rest of every cache is still NaN
+    torch.cuda.synchronize()
+    live = arena.len.cpu().numpy()
+    for c in range(arena.n_caches):
+        o, n, cp = int(arena.off_host[c]), int(live[c]), int(cap[c])
+        if n < cp:
+            assert bool(torch.isnan(arena.k[o + n:o + cp].float()).all()) and bool(torch.isnan(arena.v[o + n:o + cp].float()).all())
+            assert bool(torch.isnan(arena.score[o + n:o + cp]).all()) and bool((arena.pos[o + n:o + cp] == -1).all())
     # one eviction, judged on the device's own scores
     st = H.download(arena, w)
     kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev)

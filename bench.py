@@ -110,7 +110,7 @@ def stream_probe(torch, B, device, nbytes=1 << 32, reps=5):
     dst = torch.empty((nbytes,), dtype=torch.uint8, device=device)
     src.fill_(1)
     out = {"bytes": nbytes}
-    for mode, name in ((0, "copy"), (1, "read"), (2, "read_nt")):
+    for mode, name in ((0, "copy"), (1, "read"), (2, "read_nt"), (3, "read_nt_64_workgroups")):
         B.stream_probe(dst, src, nbytes, mode)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -255,7 +255,8 @@ int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launch
  * Measurement aid, independent of any context: streams `bytes` (a multiple of 16) through a
  * trivial kernel on `stream`.  mode 0 copies src to dst (both DEVICE, `bytes` long, 16-byte
  * aligned); modes 1 and 2 only read src, with ordinary and with non-temporal loads (dst DEVICE,
- * at least 1 KiB, is not meaningfully written).
+ * at least 1 KiB, is not meaningfully written); mode 3 is mode 2 on 64 workgroups only (what 64
+ * compute units can pull on their own).
  * Used to calibrate the HBM byte counters against a transfer of known size and to measure the
  * bandwidth a plain streaming kernel reaches on the same device.
  * Errors: EINVAL (null, misaligned, bytes not a positive multiple of 16, bad mode), EHIP.

@@ -293,7 +293,7 @@ class Arena:
 
 
 def stream_probe(dst, src, nbytes: int, mode: int, stream=None) -> None:
-    """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only, 2: read only with non-temporal loads)."""
+    """baklava_stream_probe on two torch device tensors (mode 0: copy, 1: read only, 2: read only with non-temporal loads, 3: mode 2 on 64 workgroups)."""
     _check(lib().baklava_stream_probe(dst.data_ptr(), src.data_ptr(), int(nbytes), int(mode),
                                       _stream_ptr(stream)), "baklava_stream_probe")
 

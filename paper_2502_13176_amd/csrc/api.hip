@@ -605,7 +605,7 @@ extern "C" int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out) {
 }
 
 extern "C" int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream) {
-  if (!dst || !src || bytes <= 0 || (bytes & 15) || (mode < 0 || mode > 2)) return BAKLAVA_EINVAL;
+  if (!dst || !src || bytes <= 0 || (bytes & 15) || (mode < 0 || mode > 3)) return BAKLAVA_EINVAL;
   if (((uintptr_t)dst | (uintptr_t)src) & 15) return BAKLAVA_EINVAL;
   if (!hip_ok(launch_stream_probe(dst, src, bytes, mode, (hipStream_t)stream))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;

@@ -4,7 +4,10 @@
 //
 // The read sweep gives each workgroup one contiguous 256 KiB block and keeps 8 16-byte loads per
 // thread in flight, the access shape that gave the highest read bandwidth of the shapes tried;
-// it exists with ordinary and with non-temporal loads.
+// it exists with ordinary and with non-temporal loads, and on a grid of 64 workgroups only (the rate
+// one compute unit reaches when the memory system is not the limit).
+#include <algorithm>
+
 #include "common.h"
 
 namespace baklava {
@@ -24,18 +27,21 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ ds
 template <bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(uint32_t* __restrict__ dst,
                                                           const uint4* __restrict__ src, int64_t n16) {
-  const int64_t b0 = (int64_t)blockIdx.x * kBlock16;
-  const int64_t b1 = min(b0 + kBlock16, n16);
   uint32_t acc = 0;
-  for (int64_t i = b0 + threadIdx.x; i < b1; i += 256 * kU) {
-    uint4 v[kU];
+  // a workgroup takes blocks blockIdx.x, blockIdx.x + gridDim.x, ...: one block each when the grid
+  // covers the buffer, many when the probe runs on a few workgroups only
+  for (int64_t b0 = (int64_t)blockIdx.x * kBlock16; b0 < n16; b0 += (int64_t)gridDim.x * kBlock16) {
+    const int64_t b1 = min(b0 + kBlock16, n16);
+    for (int64_t i = b0 + threadIdx.x; i < b1; i += 256 * kU) {
+      uint4 v[kU];
 #pragma unroll
-    for (int u = 0; u < kU; ++u) {
-      v[u] = make_uint4(0, 0, 0, 0);
-      if (i + u * 256 < b1) v[u] = NT ? load_nt16(src + i + u * 256) : src[i + u * 256];
+      for (int u = 0; u < kU; ++u) {
+        v[u] = make_uint4(0, 0, 0, 0);
+        if (i + u * 256 < b1) v[u] = NT ? load_nt16(src + i + u * 256) : src[i + u * 256];
+      }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-#pragma unroll
-    for (int u = 0; u < kU; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
   // a store that (for ordinary data) never happens keeps the loads alive
   if (acc == 0x9e3779b9u) dst[threadIdx.x] = acc;
@@ -51,8 +57,10 @@ hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mo
     stream_copy_kernel<<<dim3(4096), block, 0, s>>>(reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src), n16);
   else if (mode == 1)
     stream_read_kernel<false><<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
-  else
+  else if (mode == 2)
     stream_read_kernel<true><<<grid, block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
+  else  // mode 3: the same sweep on 64 workgroups only, i.e. what 64 compute units can pull on their own
+    stream_read_kernel<true><<<dim3(std::min<unsigned>(64u, grid.x)), block, 0, s>>>(reinterpret_cast<uint32_t*>(dst), reinterpret_cast<const uint4*>(src), n16);
   return hipGetLastError();
 }
 

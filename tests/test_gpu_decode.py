@@ -225,3 +225,25 @@ def test_fused_append_at_item_boundaries(kernel):
         H.check_decode_against_oracle(arena, w, post, q64, out)
         st = post
     arena.close()
+
+
+def test_stream_probe_modes():
+    """The measurement aid: the copy really copies, the read-only sweeps leave both buffers alone,
+    unknown modes and odd sizes are refused."""
+    dev = torch.device("cuda:0")
+    n = (1 << 22) + 4096 + 16                      # not a multiple of the probe's block size
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device=dev)
+    dst = torch.zeros((n,), dtype=torch.uint8, device=dev)
+    B.stream_probe(dst, src, n, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    keep = dst.clone()
+    for mode in (1, 2, 3):
+        B.stream_probe(dst, src, n, mode)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, keep)
+    for bad in (lambda: B.stream_probe(dst, src, n, 4), lambda: B.stream_probe(dst, src, n - 8, 0),
+                lambda: B.stream_probe(dst, src, 0, 1)):
+        with pytest.raises(B.BaklavaError) as e:
+            bad()
+        assert e.value.status == B.EINVAL

@@ -305,6 +305,27 @@ int baklava_layer_similarity(const void* x_in, const void* x_out, int32_t n_seq,
                              size_t workspace_bytes, void* stream);
 
 /*
+ * baklava_layer_similarity for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * per-workgroup partial sums go to a fixed device array inside the library
+ * (BAKLAVA_LAYER_STATIC_MAX_TILES floats = 256 KiB, held by every GPU the library runs on until the
+ * process ends) instead of a workspace; arguments, results and kernels are otherwise those of
+ * baklava_layer_similarity, and the results are bit-identical to it.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine).  The first call on a device looks up
+ * the array's device address; make that one call outside a capture.
+ * Limit: n_seq * ceil(T / 16) <= BAKLAVA_LAYER_STATIC_MAX_TILES, e.g. 32 layers x 32768 tokens.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams,
+ * different host threads) race on it; calls on one stream are safe.  Nothing in it has to be
+ * cleared between calls: a call only reads what it has written itself.
+ * Errors: EINVAL (as baklava_layer_similarity; device index >= 64), ECAPACITY (beyond the limit
+ * above: nothing is enqueued), EHIP.
+ */
+#define BAKLAVA_LAYER_STATIC_MAX_TILES 65536
+int baklava_layer_similarity_static(const void* x_in, const void* x_out, int32_t n_seq, int32_t T,
+                                    int32_t hidden, int32_t dtype, float* cos_out, float* sim_out,
+                                    void* stream);
+
+/*
  * Two-level allocation (host only): layer pools from the layer importances by the proportional
  * rule of baklava_alloc_proportional (bounds Hkv*lo .. Hkv*hi per layer, exact sum), then inside
  * each layer an equal split of the pool (remainder to the most important caches first, ties to the

@@ -30,7 +30,7 @@ EXPORTS = [
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
     "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance", "baklava_prefill_scores", "baklava_layer_workspace_bytes", "baklava_layer_similarity",
-    "baklava_alloc_two_level",
+    "baklava_alloc_two_level", "baklava_layer_similarity_static",
 ]
 
 
@@ -101,6 +101,8 @@ def lib() -> C.CDLL:
     L.baklava_layer_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
     L.baklava_layer_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.baklava_layer_similarity_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                  C.c_void_p, C.c_void_p, C.c_void_p]
     L.baklava_alloc_two_level.argtypes = [f64p, f64p, C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int32,
                                           C.c_double, C.c_double, i32p]
     L.baklava_prefill_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -377,3 +379,15 @@ def layer_similarity(x_in, x_out, want_cos: bool = True, stream=None):
                                           _stream_ptr(stream)), "baklava_layer_similarity")
     return sim, cos
 
+
+
+LAYER_STATIC_MAX_TILES = 65536
+
+
+def layer_similarity_static(x_in, x_out, sim, cos=None, stream=None) -> None:
+    """baklava_layer_similarity_static: as layer_similarity, but the caller passes the outputs (sim [n_seq],
+    cos [n_seq, T] or None, fp32 device tensors) and nothing is allocated, here or in the library."""
+    n_seq, T, hidden = x_in.shape
+    _check(lib().baklava_layer_similarity_static(x_in.data_ptr(), x_out.data_ptr(), n_seq, T, hidden, BF16,
+                                                 cos.data_ptr() if cos is not None else None, sim.data_ptr(),
+                                                 _stream_ptr(stream)), "baklava_layer_similarity_static")

@@ -260,6 +260,8 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
 
 }  // namespace
 
+void baklava::note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
 extern "C" int baklava_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host,

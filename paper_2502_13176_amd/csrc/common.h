@@ -126,6 +126,9 @@ struct CompactParams {
   int32_t seg_base;        // index of segs[0] in seg_split
 };
 
+// Records a failed HIP call for baklava_last_hip_error() (per host thread).
+void note_hip_error(hipError_t e);
+
 // Launchers (defined next to their kernels).  All return hipError_t of the launch.
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 // max_count: longest work item of the launch (rows); one_wave: the launch has at most one workgroup per

@@ -6,13 +6,17 @@
 // flight before the first use, non-temporal (read once); three dot products per row reduced over
 // the wavefront.  A workgroup takes 16 consecutive rows and writes the sum of their cosines; a
 // second small kernel adds the workgroup sums in a fixed order (deterministic, no atomics).
+#include <mutex>
+
+#include "baklava.h"
 #include "common.h"
 
 namespace baklava {
 
+constexpr int kRowsPerWg = 16;
+
 namespace {
 
-constexpr int kRowsPerWg = 16;
 constexpr int kWaves = 4;
 constexpr float kCosEps = 1e-8f;
 
@@ -107,3 +111,56 @@ hipError_t launch_layer_similarity(const void* x_in, const void* x_out, int n_se
 }
 
 }  // namespace baklava
+
+// ---------------------------------------------------------------------------------------------
+// The same pass for callers that cannot allocate and have no workspace to hand over: the
+// per-workgroup partial sums live in a fixed device array instead.
+// ---------------------------------------------------------------------------------------------
+
+static __device__ __align__(256) float scratch[BAKLAVA_LAYER_STATIC_MAX_TILES];
+
+namespace {
+
+// In host code the array's name is only a handle for the runtime; the device address has to be
+// asked for, once per device (every device holds its own copy of the array).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_for_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { baklava::note_hip_error(e); return BAKLAVA_EHIP; }
+  if (dev < 0 || dev >= kMaxDevices) return BAKLAVA_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) { baklava::note_hip_error(e); return BAKLAVA_EHIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BAKLAVA_OK;
+}
+
+}  // namespace
+
+extern "C" int baklava_layer_similarity_static(const void* x_in, const void* x_out, int32_t n_seq, int32_t T,
+                                               int32_t hidden, int32_t dtype, float* cos_out, float* sim_out,
+                                               void* stream) {
+  if (!x_in || !x_out || !sim_out) return BAKLAVA_EINVAL;
+  if (n_seq <= 0 || T <= 0 || hidden <= 0 || hidden % 8 || dtype != BAKLAVA_BF16) return BAKLAVA_EINVAL;
+  if (((uintptr_t)x_in | (uintptr_t)x_out) & 15) return BAKLAVA_EINVAL;
+  if (((uintptr_t)sim_out | (uintptr_t)cos_out) & 3) return BAKLAVA_EINVAL;
+  const int64_t tiles = (int64_t)n_seq * (((int64_t)T + baklava::kRowsPerWg - 1) / baklava::kRowsPerWg);
+  if (tiles > BAKLAVA_LAYER_STATIC_MAX_TILES) return BAKLAVA_ECAPACITY;
+  float* tile_sum = nullptr;
+  const int st = scratch_for_current_device(&tile_sum);
+  if (st != BAKLAVA_OK) return st;
+  // Every partial sum the second kernel reads is written by the first one in this call, so nothing
+  // has to be cleared; what earlier calls left in the array is never read.
+  const hipError_t e = baklava::launch_layer_similarity(x_in, x_out, n_seq, T, hidden, cos_out, sim_out, tile_sum,
+                                                        (hipStream_t)stream);
+  if (e != hipSuccess) { baklava::note_hip_error(e); return BAKLAVA_EHIP; }
+  return BAKLAVA_OK;
+}

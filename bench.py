@@ -41,6 +41,7 @@ def parse_args():
                     help="work items per layer launch to aim for (-1 = library default, 0 = off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-track", action="store_true", help="do not accumulate attention scores (long workload)")
+    ap.add_argument("--track", action="store_true", help="accumulate attention scores whatever the workload")
     ap.add_argument("--no-compaction", action="store_true", help="attention and appends only")
     ap.add_argument("--keep-pct", type=int, default=0,
                     help="percent of the context kept globally instead of the workload's own (the other reading of "
@@ -356,7 +357,7 @@ def main():
     if args.keep_pct > 0:
         w = synth.shrink(w, keep_pct=args.keep_pct)
     budgets = synth.budgets_for(w, B.alloc_proportional)
-    track = w.scores == "kernel" and not args.no_track
+    track = (w.scores == "kernel" or args.track) and not args.no_track
     policy = B.POLICY_STREAMING if args.policy == "streaming" else B.POLICY_SCORE
     arena = B.Arena(w.L, w.Hq, w.Hkv, w.D, w.batch, w.dtype, budgets, w.slack, w.sink, w.recent,
                     policy, track)

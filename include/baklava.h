@@ -39,7 +39,8 @@ enum {
   BAKLAVA_EINFEASIBLE = 2, /* budgets cannot be met: m*lo > B, m*hi < B, budget < sink + recent     */
   BAKLAVA_ECAPACITY = 3,   /* an append would exceed a cache's capacity; workspace too small        */
   BAKLAVA_EHIP = 4,        /* a HIP runtime call failed; see baklava_last_hip_error()               */
-  BAKLAVA_ESTATE = 5       /* call order violated, e.g. attention over an empty cache               */
+  BAKLAVA_ESTATE = 5,      /* call order violated, e.g. attention over an empty cache               */
+  BAKLAVA_ENOMEM = 6       /* a host-side allocation of the library failed                          */
 };
 
 enum { BAKLAVA_BF16 = 0, BAKLAVA_F32 = 1 };
@@ -131,7 +132,8 @@ typedef struct {
   int32_t dtype;          /* BAKLAVA_BF16 or BAKLAVA_F32: element type of k, v and of q / k_new / v_new */
   int32_t sink, recent;   /* rows at the front / back of a cache that eviction never removes        */
   int32_t policy;         /* BAKLAVA_POLICY_*                                                        */
-  int32_t track_scores;   /* 1: decode_attn adds each token's attention weights to `score`          */
+  int32_t track_scores;   /* 1: attention calls add each token's attention weights to `score`; see
+                             baklava_flush_scores for when the plane is up to date                  */
   void* k;                /* DEVICE [total_tokens, D] row-major, 16-byte aligned                     */
   void* v;                /* DEVICE [total_tokens, D]                                                */
   float* score;           /* DEVICE [total_tokens] accumulated attention per cached token            */
@@ -146,8 +148,8 @@ typedef struct {
 
 /*
  * Bytes of device workspace a context with this description needs (split partials, work-item
- * tables, kept-index lists, halo rows of the eviction move, and the logit stash when
- * track_scores is set).  Pointer fields of `desc` are ignored.  cap_host HOST [n_caches],
+ * tables, kept-index lists, halo rows of the eviction move, and with track_scores the query rows
+ * and softmax normalisers of each cache's latest attention call).  Pointer fields of `desc` are ignored.  cap_host HOST [n_caches],
  * budget_host HOST [L*Hkv].  Returns 0 on invalid arguments.
  */
 size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host,
@@ -211,7 +213,8 @@ int baklava_append(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, c
  *   out[hq] = softmax(q[hq] . K_c^T / sqrt(D)) V_c,  c = the cache of KV head hq / G.
  * q   DEVICE [layer_count, batch, Hq, D] in the context's dtype, 16-byte aligned.
  * out DEVICE [layer_count, batch, Hq, D] fp32, fully overwritten.
- * With track_scores, score[j] += sum over the G query heads of the softmax weight of row j.
+ * With track_scores, score[j] += sum over the G query heads of the softmax weight of row j; the
+ * addition may be deferred to a later attention call over the same layer (baklava_flush_scores).
  * Accumulation is fp32 throughout.
  * Errors: EINVAL, ESTATE (a cache in range is empty).
  */
@@ -227,6 +230,47 @@ int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_cou
 int baklava_append_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
                                const void* k_new, const void* v_new, int32_t token_pos,
                                const void* q, float* out, void* stream);
+
+/*
+ * baklava_append_decode_attn for a step that is captured once into a HIP graph and replayed: nothing
+ * the step needs is baked into the launch.  The new row's position is read on the device from
+ * *token_pos_dev (DEVICE int32, 4-byte aligned; the caller advances it between replays, e.g. with a
+ * kernel of its own inside the graph), and whether a cache still has room is decided on the device
+ * from its length and capacity tables: a full cache receives no row, is attended as it stands, and
+ * raises a status word that baklava_sync_lengths reports.  The host mirror of the lengths is
+ * neither consulted nor advanced; call baklava_sync_lengths before the next call that relies on it
+ * (baklava_append, baklava_append_decode_attn, baklava_decode_attn's empty-cache check,
+ * baklava_lengths).  Only enqueues kernels: no memset, no copy, no synchronisation.
+ * Errors: EINVAL.
+ */
+int baklava_append_decode_attn_replay(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                                      const void* k_new, const void* v_new, const int32_t* token_pos_dev,
+                                      const void* q, float* out, void* stream);
+
+/*
+ * Reads the device's length table back into the host mirror and returns ECAPACITY if, since the
+ * last such call, a fused append found a cache full (the status word is then cleared).
+ * Synchronises `stream`; not to be captured.
+ */
+int baklava_sync_lengths(baklava_ctx* ctx, void* stream);
+
+/*
+ * Score tracking keeps, per cached row, the attention it has received so far (summed over the
+ * query heads of its group and over decode steps: the cumulative-attention statistic of the
+ * heavy-hitter policies the paper's Related Work cites).  A row's weight in a call needs the
+ * softmax normaliser of its whole cache, which is only known when the call is over, so the weights
+ * of a call are added by a later attention call over the same layer, which streams the same K
+ * rows anyway (a cache keeps up to 4 calls on record and adds them together), or by this
+ * function: a pass over the K rows of the layer range alone.  After it the score plane of the
+ * range holds every weight up to the latest call; without it the plane lacks at most the weights
+ * of the calls on record, never anything else.  baklava_compact does this itself before it ranks
+ * rows; baklava_reset and baklava_set_lengths drop what is on record.  The rows a recorded call
+ * attended must keep their places until its weights are added: the library's own calls see to
+ * that; a caller that rewrites arena rows itself calls baklava_set_lengths afterwards.
+ * No-op without track_scores.  Enqueues kernels on `stream`, does not synchronise.
+ * Errors: EINVAL, EHIP.
+ */
+int baklava_flush_scores(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, void* stream);
 
 /*
  * Eviction down to budget (f_evict, Eqs. 5-6: evicted rows vanish, survivors keep their order)

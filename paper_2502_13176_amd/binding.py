@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 # BAKLAVA_LIB lets a tuning run load a differently built copy of the same library.
 LIB_PATH = os.environ.get("BAKLAVA_LIB") or os.path.join(HERE, "libbaklava.so")
 
-OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE = range(6)
+OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE, ENOMEM = range(7)
 BF16, F32 = 0, 1
 POLICY_SCORE, POLICY_STREAMING = 0, 1
 OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL, OPT_CHUNK_TOKENS_WHOLE, OPT_TARGET_ITEMS, OPT_TARGET_ITEMS_WHOLE = 1, 2, 3, 4, 5, 6
@@ -30,7 +30,8 @@ EXPORTS = [
     "baklava_destroy", "baklava_set_option", "baklava_reset", "baklava_set_lengths",
     "baklava_append", "baklava_decode_attn", "baklava_append_decode_attn", "baklava_compact", "baklava_lengths", "baklava_profile_read",
     "baklava_stream_probe", "baklava_profile_workspace_bytes", "baklava_profile_similarity", "baklava_kv_importance", "baklava_prefill_scores", "baklava_layer_workspace_bytes", "baklava_layer_similarity",
-    "baklava_alloc_two_level", "baklava_layer_similarity_static",
+    "baklava_alloc_two_level", "baklava_layer_similarity_static", "baklava_append_decode_attn_replay",
+    "baklava_sync_lengths", "baklava_flush_scores",
 ]
 
 
@@ -87,6 +88,10 @@ def lib() -> C.CDLL:
     L.baklava_append.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     L.baklava_append_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+    L.baklava_append_decode_attn_replay.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p, C.c_void_p]
+    L.baklava_sync_lengths.argtypes = [C.c_void_p, C.c_void_p]
+    L.baklava_flush_scores.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     L.baklava_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     L.baklava_compact.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     L.baklava_lengths.argtypes = [C.c_void_p, i32p]
@@ -273,6 +278,20 @@ class Arena:
         _check(lib().baklava_append_decode_attn(self.ctx, layer_begin, layer_count, k_new.data_ptr(),
                                                 v_new.data_ptr(), int(token_pos), q.data_ptr(), out.data_ptr(),
                                                 _stream_ptr(stream)), "baklava_append_decode_attn")
+
+    def append_decode_attn_replay(self, layer_begin: int, layer_count: int, k_new, v_new, token_pos_dev, q, out,
+                                  stream=None) -> None:
+        _check(lib().baklava_append_decode_attn_replay(self.ctx, layer_begin, layer_count, k_new.data_ptr(),
+                                                       v_new.data_ptr(), token_pos_dev.data_ptr(), q.data_ptr(),
+                                                       out.data_ptr(), _stream_ptr(stream)),
+               "baklava_append_decode_attn_replay")
+
+    def sync_lengths(self, stream=None) -> None:
+        _check(lib().baklava_sync_lengths(self.ctx, _stream_ptr(stream)), "baklava_sync_lengths")
+
+    def flush_scores(self, layer_begin: int, layer_count: int, stream=None) -> None:
+        _check(lib().baklava_flush_scores(self.ctx, layer_begin, layer_count, _stream_ptr(stream)),
+               "baklava_flush_scores")
 
     def decode_attn(self, layer_begin: int, layer_count: int, q, out, stream=None) -> None:
         _check(lib().baklava_decode_attn(self.ctx, layer_begin, layer_count, q.data_ptr(), out.data_ptr(),

@@ -39,8 +39,8 @@ int64_t count_items(const int32_t* cap, int64_t n_caches, int chunk) {
 struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
   size_t items[2], multi[2];
-  size_t part_o, part_ml, final_ml, logits, kept, info, order_all, order_layer;
-  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, stash_off, total;
+  size_t part_o, part_ml, final_ml, lag_q, lag_ml, lag_n, lag_cnt, status, kept, info, order_all, order_layer;
+  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, total;
   int64_t n_segs, halo_rows;
   int64_t max_items;
 };
@@ -93,10 +93,14 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
   w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
   w.final_ml = o;     o = align256(o + (size_t)n_caches * G * 2 * 4);
-  int64_t stash_floats = 0;
-  for (int64_t c = 0; c < n_caches; ++c) stash_floats += (int64_t)G * (((int64_t)cap[c] + 31) / 32 * 32);
-  w.logits = o;       o = align256(o + (d->track_scores ? (size_t)stash_floats * 4 : 0));
-  w.stash_off = o;    o = align256(o + (size_t)n_caches * 8);
+  // the record of the pending calls of every cache (score tracking): 16 packed query rows, their
+  // (max, 1/sum), the rows each call saw, the count of pending calls per head
+  const bool track = d->track_scores != 0;
+  w.lag_q = o;        o = align256(o + (track ? (size_t)n_caches * 16 * row_bytes : 0));
+  w.lag_ml = o;       o = align256(o + (track ? (size_t)n_caches * 16 * 2 * 4 : 0));
+  w.lag_n = o;        o = align256(o + (size_t)n_caches * 4 * 4);
+  w.lag_cnt = o;      o = align256(o + (size_t)n_caches * G * 4);
+  w.status = o;       o = align256(o + 256);
   w.kept = o;         o = align256(o + (size_t)total_tokens * 4);
   w.info = o;         o = align256(o + (size_t)n_caches * sizeof(CompactInfo));
   w.order_all = o;    o = align256(o + (size_t)n_caches * 4);
@@ -128,6 +132,7 @@ struct baklava_ctx {
   int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
   int32_t target_items_whole;  // > 0: the same for launches over the whole model
   int32_t n_cus;               // compute units of the device
+  int32_t lag_gp_log2;         // score tracking: log2 of G rounded up to 4, 8 or 16 (rows a call takes in a record)
   struct Schedule {
     int32_t chunk = 0;
     std::vector<int32_t> max_count;    // layer -> longest work item of the layer, rows
@@ -190,19 +195,80 @@ bool range_ok(const baklava_ctx* ctx, int32_t lb, int32_t lc) {
   return lb >= 0 && lc > 0 && (int64_t)lb + lc <= ctx->d.L;
 }
 
+// The weights of the calls on record go to the score plane now (see DecodeParams): a pass over the
+// K rows of the layer range, after which the records are empty.  Only the MFMA attention kernel
+// (bf16, D = 128) leaves calls on record.
+int flush_records(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, hipStream_t s) {
+  if (!ctx->d.track_scores || !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_OK;
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  const int which = (layer_begin == 0 && layer_count == ctx->d.L) ? 1 : 0;
+  const baklava_ctx::Schedule& sc = ctx->sched[which];
+  const int32_t i0 = sc.cib[c0], i1 = sc.cib[c1];
+  DecodeParams p{};
+  p.k = ctx->d.k; p.score = ctx->d.score;
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]) + i0;
+  p.lag_q = ctx->ws + ctx->plan.lag_q;
+  p.lag_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.lag_ml);
+  p.lag_n = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_n);
+  p.lag_cnt = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_cnt);
+  p.G = ctx->G; p.lag_gp_log2 = ctx->lag_gp_log2;
+  p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
+  if (!hip_ok(launch_score_flush_mfma(p, i1 - i0, s))) return BAKLAVA_EHIP;
+  if (!hip_ok(launch_fill_i32(p.lag_cnt + c0 * ctx->G, 0, (c1 - c0) * ctx->G, s))) return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
+// The vector-ALU path's score update for the call that has just been enqueued with query `q`.
+int score_pass(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, const void* q, hipStream_t s) {
+  const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
+  const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
+  const int which = (layer_begin == 0 && layer_count == ctx->d.L) ? 1 : 0;
+  const baklava_ctx::Schedule& sc = ctx->sched[which];
+  const int32_t i0 = sc.cib[c0], i1 = sc.cib[c1];
+  ScoreParams p;
+  p.k = ctx->d.k; p.q = q;
+  p.ml = reinterpret_cast<const float*>(ctx->ws + ctx->plan.final_ml);
+  p.len = ctx->d.len;
+  p.items = reinterpret_cast<const Item*>(ctx->ws + ctx->plan.items[which]) + i0;
+  p.score = ctx->d.score;
+  p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv;
+  p.cache_begin = (int32_t)c0;
+  p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
+  const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
+                                            sc.max_count.begin() + layer_begin + layer_count);
+  if (!hip_ok(launch_score_pass(p, ctx->d.dtype, ctx->d.D, i1 - i0, longest, s))) return BAKLAVA_EHIP;
+  return BAKLAVA_OK;
+}
+
+// host_lengths: the host mirror of the lengths is checked and advanced (the calls that take the token
+// position by value); otherwise the device tables alone decide and evolve.
 int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, const void* k_new,
-                const void* v_new, int32_t token_pos, const void* q, float* out, void* stream) {
+                const void* v_new, int32_t token_pos, const int32_t* token_pos_dev, bool host_lengths,
+                const void* q, float* out, void* stream) {
   const bool fused = k_new != nullptr;
   const int64_t c0 = (int64_t)layer_begin * ctx->cpl;
   const int64_t c1 = c0 + (int64_t)layer_count * ctx->cpl;
-  for (int64_t c = c0; c < c1; ++c) {
-    if (fused && ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
-    if (!fused && ctx->len[c] <= 0) return BAKLAVA_ESTATE;
+  if (host_lengths) {
+    for (int64_t c = c0; c < c1; ++c) {
+      if (fused && ctx->len[c] >= ctx->cap[c]) return BAKLAVA_ECAPACITY;
+      if (!fused && ctx->len[c] <= 0) return BAKLAVA_ESTATE;
+    }
   }
   const bool whole = layer_begin == 0 && layer_count == ctx->d.L;
   const int which = whole ? 1 : 0;
   const baklava_ctx::Schedule& sc = ctx->sched[which];
   const int32_t i0 = sc.cib[c0], i1 = sc.cib[c1];
+  hipStream_t s = (hipStream_t)stream;
+  const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
+  const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
+  const bool track = ctx->d.track_scores != 0;
+  // The vector-ALU kernel adds its weights right after the call; weights an earlier MFMA call left
+  // pending come first, so that the scores grow in the order of the calls.
+  if (track && !use_mfma) {
+    const int st = flush_records(ctx, layer_begin, layer_count, s);
+    if (st != BAKLAVA_OK) return st;
+  }
   DecodeParams p;
   p.k = ctx->d.k; p.v = ctx->d.v; p.q = q; p.out = out;
   p.off = ctx->d.off; p.len = ctx->d.len;
@@ -212,24 +278,28 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   p.part_o = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_o);
   p.part_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.part_ml);
   p.final_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.final_ml);
-  p.logits = reinterpret_cast<float*>(ctx->ws + ctx->plan.logits);
-  p.stash_off = reinterpret_cast<const int64_t*>(ctx->ws + ctx->plan.stash_off);
+  p.lag_q = ctx->ws + ctx->plan.lag_q;
+  p.lag_ml = reinterpret_cast<float*>(ctx->ws + ctx->plan.lag_ml);
+  p.lag_n = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_n);
+  p.lag_cnt = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_cnt);
   p.cap = ctx->d.cap;
   p.score = ctx->d.score;
   p.pos = ctx->d.pos;
   const int32_t m0 = sc.multi_begin[layer_begin], m1 = sc.multi_begin[layer_begin + layer_count];
   p.multi = reinterpret_cast<const MultiCache*>(ctx->ws + ctx->plan.multi[which]) + m0;
   p.k_new = k_new; p.v_new = v_new;
+  p.token_pos_dev = token_pos_dev;
+  p.status = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.status);
   p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
   p.cache_begin = (int32_t)c0;
-  p.track = ctx->d.track_scores ? 1 : 0;
+  p.lag = (track && use_mfma) ? 1 : 0;
+  p.lag_batch = 16 >> ctx->lag_gp_log2 > 4 ? 4 : 16 >> ctx->lag_gp_log2;
+  p.lag_gp_log2 = ctx->lag_gp_log2;
+  p.ring_slots = 0;
   p.fused_append = fused ? 1 : 0;
   p.token_pos = token_pos;
   p.row_bytes = ctx->row_bytes;
   p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
-  hipStream_t s = (hipStream_t)stream;
-  const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
-  const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   if (ctx->time_kernel) {
     while (ctx->ev.size() < 2 * (ctx->ev_used + 1)) {
@@ -243,7 +313,6 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   }
   const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
                                             sc.max_count.begin() + layer_begin + layer_count);
-  p.stash_slots = 0;
   hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, longest, i1 - i0 <= ctx->n_cus, s)
                           : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
   if (!hip_ok(e)) return BAKLAVA_EHIP;
@@ -252,9 +321,9 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
     ctx->ev_used += 1;
   }
   if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
-  if (fused)
+  if (fused && host_lengths)
     for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
-  if (p.track && !hip_ok(launch_score_update(p, i1 - i0, longest, s))) return BAKLAVA_EHIP;
+  if (track && !use_mfma) return score_pass(ctx, layer_begin, layer_count, q, s);
   return BAKLAVA_OK;
 }
 
@@ -292,17 +361,22 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
     const int need = desc->policy == BAKLAVA_POLICY_SCORE ? desc->sink + desc->recent : desc->sink;
     if (budget_host[i] < need) return BAKLAVA_EINFEASIBLE;
   }
+  // The arena must be packed as baklava_layout lays it out (off[c] = capacities before c): the
+  // workspace planes that run parallel to the arena (kept lists) are indexed by the same offsets.
+  int64_t packed = 0;
   for (int64_t c = 0; c < n_caches; ++c) {
-    if (cap_host[c] < 0 || off_host[c] < 0) return BAKLAVA_EINVAL;
+    if (cap_host[c] < 0 || off_host[c] != packed) return BAKLAVA_EINVAL;
+    packed += cap_host[c];
     if (len_host && (len_host[c] < 0 || len_host[c] > cap_host[c])) return BAKLAVA_ECAPACITY;
   }
   baklava_ctx* ctx = new (std::nothrow) baklava_ctx();
-  if (!ctx) return BAKLAVA_EINVAL;
+  if (!ctx) return BAKLAVA_ENOMEM;
   ctx->d = *desc;
   ctx->n_caches = n_caches;
   ctx->cpl = desc->batch * desc->Hkv;
   ctx->G = desc->Hq / desc->Hkv;
   ctx->row_bytes = desc->D * (desc->dtype == BAKLAVA_BF16 ? 2 : 4);
+  ctx->lag_gp_log2 = ctx->G <= 4 ? 2 : ctx->G <= 8 ? 3 : 4;
   ctx->off.assign(off_host, off_host + n_caches);
   ctx->cap.assign(cap_host, cap_host + n_caches);
   if (len_host) ctx->len.assign(len_host, len_host + n_caches);
@@ -348,18 +422,11 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
     delete ctx;
     return BAKLAVA_EHIP;
   }
-  // Where each cache's logit stash starts (floats).
-  {
-    std::vector<int64_t> so(n_caches);
-    int64_t acc = 0;
-    for (int64_t c = 0; c < n_caches; ++c) {
-      so[c] = acc;
-      acc += (int64_t)ctx->G * (((int64_t)ctx->cap[c] + 31) / 32 * 32);
-    }
-    if (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.stash_off, so.data(), n_caches * 8, hipMemcpyHostToDevice))) {
-      delete ctx;
-      return BAKLAVA_EHIP;
-    }
+  // No call is pending for the score pass, and the status word is clear.
+  if (!hip_ok(hipMemset(ctx->ws + ctx->plan.lag_cnt, 0, (size_t)n_caches * ctx->G * 4)) ||
+      !hip_ok(hipMemset(ctx->ws + ctx->plan.status, 0, 256))) {
+    delete ctx;
+    return BAKLAVA_EHIP;
   }
   // Segment table of the eviction move (depends on budgets and capacities only).
   {
@@ -456,6 +523,9 @@ extern "C" int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int6
 extern "C" int baklava_reset(baklava_ctx* ctx, void* stream) {
   if (!ctx) return BAKLAVA_EINVAL;
   if (!hip_ok(launch_fill_i32(ctx->d.len, 0, ctx->n_caches, (hipStream_t)stream))) return BAKLAVA_EHIP;
+  if (!hip_ok(launch_fill_i32(reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_cnt), 0, ctx->n_caches * ctx->G,
+                              (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
   std::fill(ctx->len.begin(), ctx->len.end(), 0);
   return BAKLAVA_OK;
 }
@@ -467,6 +537,10 @@ extern "C" int baklava_set_lengths(baklava_ctx* ctx, const int32_t* len_host, vo
     if (len_host[c] > ctx->cap[c]) return BAKLAVA_ECAPACITY;
   }
   ctx->len.assign(len_host, len_host + ctx->n_caches);
+  // Weights of a call over the old contents are not owed to the new ones.
+  if (!hip_ok(launch_fill_i32(reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_cnt), 0, ctx->n_caches * ctx->G,
+                              (hipStream_t)stream)))
+    return BAKLAVA_EHIP;
   // The mirror is the staging buffer: wait for the copy so that later appends may change it.
   if (!hip_ok(hipMemcpyAsync(ctx->d.len, ctx->len.data(), ctx->n_caches * 4, hipMemcpyHostToDevice,
                              (hipStream_t)stream)))
@@ -487,6 +561,7 @@ extern "C" int baklava_append(baklava_ctx* ctx, int32_t layer_begin, int32_t lay
   p.k = ctx->d.k; p.v = ctx->d.v; p.score = ctx->d.score; p.pos = ctx->d.pos;
   p.off = ctx->d.off; p.cap = ctx->d.cap; p.len = ctx->d.len;
   p.k_new = k_new; p.v_new = v_new;
+  p.token_pos_dev = nullptr;
   p.cache_begin = (int32_t)c0; p.token_pos = token_pos; p.row_bytes = ctx->row_bytes;
   if (!hip_ok(launch_append(p, (int)(c1 - c0), (hipStream_t)stream))) return BAKLAVA_EHIP;
   for (int64_t c = c0; c < c1; ++c) ctx->len[c] += 1;
@@ -497,7 +572,7 @@ extern "C" int baklava_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_
                                    const void* q, float* out, void* stream) {
   if (!ctx || !q || !out || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
   if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return BAKLAVA_EINVAL;
-  return decode_impl(ctx, layer_begin, layer_count, nullptr, nullptr, 0, q, out, stream);
+  return decode_impl(ctx, layer_begin, layer_count, nullptr, nullptr, 0, nullptr, true, q, out, stream);
 }
 
 extern "C" int baklava_append_decode_attn(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
@@ -505,7 +580,37 @@ extern "C" int baklava_append_decode_attn(baklava_ctx* ctx, int32_t layer_begin,
                                           const void* q, float* out, void* stream) {
   if (!ctx || !q || !out || !k_new || !v_new || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
   if (((uintptr_t)q | (uintptr_t)out | (uintptr_t)k_new | (uintptr_t)v_new) & 15) return BAKLAVA_EINVAL;
-  return decode_impl(ctx, layer_begin, layer_count, k_new, v_new, token_pos, q, out, stream);
+  return decode_impl(ctx, layer_begin, layer_count, k_new, v_new, token_pos, nullptr, true, q, out, stream);
+}
+
+extern "C" int baklava_append_decode_attn_replay(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
+                                                 const void* k_new, const void* v_new,
+                                                 const int32_t* token_pos_dev, const void* q, float* out,
+                                                 void* stream) {
+  if (!ctx || !q || !out || !k_new || !v_new || !token_pos_dev || !range_ok(ctx, layer_begin, layer_count))
+    return BAKLAVA_EINVAL;
+  if (((uintptr_t)q | (uintptr_t)out | (uintptr_t)k_new | (uintptr_t)v_new) & 15) return BAKLAVA_EINVAL;
+  if ((uintptr_t)token_pos_dev & 3) return BAKLAVA_EINVAL;
+  return decode_impl(ctx, layer_begin, layer_count, k_new, v_new, 0, token_pos_dev, false, q, out, stream);
+}
+
+extern "C" int baklava_sync_lengths(baklava_ctx* ctx, void* stream) {
+  if (!ctx) return BAKLAVA_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  int32_t status = 0;
+  int32_t* status_dev = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.status);
+  if (!hip_ok(hipMemcpyAsync(ctx->len.data(), ctx->d.len, ctx->n_caches * 4, hipMemcpyDeviceToHost, s)) ||
+      !hip_ok(hipMemcpyAsync(&status, status_dev, 4, hipMemcpyDeviceToHost, s)) ||
+      !hip_ok(hipStreamSynchronize(s)))
+    return BAKLAVA_EHIP;
+  if (status == 0) return BAKLAVA_OK;
+  if (!hip_ok(launch_fill_i32(status_dev, 0, 1, s))) return BAKLAVA_EHIP;
+  return BAKLAVA_ECAPACITY;
+}
+
+extern "C" int baklava_flush_scores(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, void* stream) {
+  if (!ctx || !range_ok(ctx, layer_begin, layer_count)) return BAKLAVA_EINVAL;
+  return flush_records(ctx, layer_begin, layer_count, (hipStream_t)stream);
 }
 
 extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
@@ -534,6 +639,11 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
   p.halo_score = reinterpret_cast<float*>(ctx->ws + ctx->plan.halo_score);
   p.halo_pos = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.halo_pos);
   hipStream_t s = (hipStream_t)stream;
+  // The selection ranks rows by their scores: weights still owed to them are added first.
+  {
+    const int st = flush_records(ctx, layer_begin, layer_count, s);
+    if (st != BAKLAVA_OK) return st;
+  }
   if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
   if (!hip_ok(launch_compact_move(p, s1 - s0, s))) return BAKLAVA_EHIP;
   for (int64_t c = c0; c < c1; ++c) {

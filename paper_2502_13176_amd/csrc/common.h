@@ -56,27 +56,51 @@ struct DecodeParams {
   const Item* items;               // work items of the launched range, in launch order
   float* part_o;                   // [n_items, G, D] un-normalised partial outputs
   float* part_ml;                  // [n_items, G, 2]  (running max in log2 units, sum)
-  float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum)
-  float* logits;                   // scaled logits in log2 units (track_scores): cache c owns
-                                   // ceil(cap_c / 32) blocks of [G][32] floats starting at float
-                                   // offset stash_off[c]; row j of head g sits at
-                                   // (j / 32) * 32 G + 32 g + j % 32, so a 32-row slab is one
-                                   // contiguous, 128-byte aligned run of G lines
-  const int64_t* stash_off;
+  float* final_ml;                 // [n_caches, G, 2] (global max, 1 / global sum) of the latest call
+  // Score tracking, MFMA kernel: the weights of a call are added to the score plane by a later
+  // call over the same caches (or by the score pass that baklava_flush_scores launches), because
+  // only then are the softmax normalisers known to every work item.  Each cache keeps a record of
+  // up to lag_batch pending calls; their query rows are packed into one 16-row operand (call s,
+  // head g -> row s * Gp + g, Gp = G rounded up to 4, 8 or 16), so that one extra matrix product
+  // per slab serves all of them.  A call that finds lag_batch calls pending adds their weights and
+  // starts the record again with itself.
+  void* lag_q;                     // [n_caches, 16, D] packed query rows of the pending calls
+  float* lag_ml;                   // [n_caches, 16, 2] their (max, 1 / sum), same row numbering
+  int32_t* lag_n;                  // [n_caches, 4] rows that were live at pending call s
+  int32_t* lag_cnt;                // [n_caches, G] pending calls (one counter per head, all equal:
+                                   // each block of the combine kernel reads and writes its own)
   const int32_t* cap;
   float* score;
   int32_t* pos;
   const MultiCache* multi;         // caches of the launched range that have more than one work item
   const void* k_new;               // fused append: [caches of the range, D] rows to add first
   const void* v_new;
+  const int32_t* token_pos_dev;    // fused append: the new row's position, read on the device (or null)
+  int32_t* status;                 // device status word: bit 0 = a fused append found its cache full
   int32_t G, Hq, Hkv, batch;
   int32_t cache_begin;             // first cache id of the launched range
-  int32_t track;
-  int32_t stash_slots;             // MFMA kernel, score tracking: slabs per wavefront kept in LDS (0: none)
+  int32_t lag;                     // 1: record this call, apply the pending ones when due (MFMA kernel)
+  int32_t lag_batch;               // calls a record holds: 16 / Gp, at most 4
+  int32_t lag_gp_log2;             // log2(Gp)
+  int32_t ring_slots;              // MFMA kernel, lag: slabs per wavefront whose new scores wait in LDS
   int32_t fused_append;            // 1: every cache of the range first receives its new row
   int32_t token_pos;
   int32_t row_bytes;
   float scale_log2e;               // log2(e) / sqrt(D)
+};
+
+// Score pass of the vector-ALU path over the K rows alone, right after its attention call:
+// score_j += sum_g 2^(q_g . k_j scale - M_g) / L_g over the live rows of every cache of the range.
+struct ScoreParams {
+  const void* k;
+  const void* q;                   // [layer_count, batch, Hq, D], the call's query rows
+  const float* ml;                 // final_ml of the call
+  const int32_t* len;
+  const Item* items;
+  float* score;
+  int32_t G, Hq, Hkv;
+  int32_t cache_begin;
+  float scale_log2e;
 };
 
 struct AppendParams {
@@ -89,6 +113,7 @@ struct AppendParams {
   int32_t* len;
   const void* k_new;
   const void* v_new;
+  const int32_t* token_pos_dev;  // the row's position, read on the device (or null: token_pos)
   int32_t cache_begin;
   int32_t token_pos;
   int32_t row_bytes;
@@ -132,9 +157,12 @@ void note_hip_error(hipError_t e);
 // Launchers (defined next to their kernels).  All return hipError_t of the launch.
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 // max_count: longest work item of the launch (rows); one_wave: the launch has at most one workgroup per
-// compute unit, so a workgroup may take the whole LDS (score tracking keeps its logits there)
+// compute unit, so a workgroup may take the whole LDS (score tracking keeps its new scores there)
 hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, int max_count, bool one_wave, hipStream_t s);
 hipError_t prepare_decode_mfma();
+// the weights of the calls on record, from the K rows alone (bf16, D = 128; needs only the lag_*,
+// k, score, items, G and scale fields)
+hipError_t launch_score_flush_mfma(const DecodeParams& p, int n_items, hipStream_t s);
 hipError_t launch_profile_similarity(const void* q, const void* k, const void* v, int batch, int Hq, int Hkv,
                                      int T, float* cos_out, float* sim_out, float* lse_out, float* tile_sum,
                                      hipStream_t s);
@@ -144,7 +172,7 @@ hipError_t launch_prefill_scores(const void* q, const void* k, const float* lse,
                                  int batch, int Hq, int Hkv, int T, float* score, hipStream_t s);
 hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t s);
 // max_count: the largest row count of a work item in the launched range (or a bound on it)
-hipError_t launch_score_update(const DecodeParams& p, int n_items, int max_count, hipStream_t s);
+hipError_t launch_score_pass(const ScoreParams& p, int dtype, int D, int n_items, int max_count, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
 hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s);

@@ -24,6 +24,18 @@
 //
 // Each wavefront of a workgroup streams its own 32-row slabs and owns a private LDS region: there
 // is no barrier inside the loop.
+//
+// Score tracking (cumulative attention per cached row) rides on the same stream, a few calls late:
+// a row's weight needs the softmax normaliser of the whole cache, which no work item knows before
+// the call is over.  So each call records its query rows and final (max, 1/sum) per cache, and a
+// later call -- whose K rows pass through LDS anyway -- forms the recorded calls' logits with one
+// more product that reuses the K operands (the matrix pipe is < 10% busy), turns them into
+// normalised weights and adds them to the scores.  The G query heads fill only G of the 16 rows of
+// a matrix operand, so the rows of up to 16 / G recorded calls are packed into one operand and
+// the scores are touched only on every (16 / G)-th call (at most every 4th).  On such a call the
+// scores of a slab are read with the slab and the new values wait in LDS until the work item is
+// done, so the extra HBM writes (4 bytes per row) fall at the end of a launch instead of between
+// the K/V reads.
 #include "common.h"
 #include "decode_tail.h"
 
@@ -56,20 +68,74 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_cast(bf16x8_t, x); }
 
+// The recorded calls of one cache as a lane sees them.  The packed query rows are the A operand of
+// the product S' = Q' K^T (lane (m, j), chunk c holds row m, elements 32c + 8j .. +8); the product
+// leaves lane (row, jg) with the logits of packed rows 4*jg .. 4*jg+3, which all belong to one
+// call, so the lane keeps their (max, 1/sum) and the number of rows that call saw.
+struct Record {
+  bf16x8_t q[4];
+  float m[4], inv[4];
+  int n_slot;
+};
+
+__device__ __forceinline__ void load_record(const DecodeParams& p, int c, int G, int pending, int n16, int jg,
+                                            Record& r) {
+  const int gp_mask = (1 << p.lag_gp_log2) - 1;
+  const unsigned char* lq = reinterpret_cast<const unsigned char*>(p.lag_q) + (int64_t)c * 16 * (kD * 2);
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) {
+    u32x4_t raw = {0u, 0u, 0u, 0u};  // rows beyond the G heads of a call, calls not on record: zero
+    if ((n16 & gp_mask) < G && (n16 >> p.lag_gp_log2) < pending)
+      raw = *reinterpret_cast<const u32x4_t*>(lq + n16 * (kD * 2) + ch * 64 + jg * 16);
+    r.q[ch] = as_bf16x8(raw);
+  }
+  const int slot = (4 * jg) >> p.lag_gp_log2;
+  r.n_slot = 0;
+  if (slot < pending) r.n_slot = p.lag_n[(int64_t)c * 4 + slot];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = 4 * jg + i;
+    r.m[i] = 0.f;
+    r.inv[i] = 0.f;
+    if ((m & gp_mask) < G && slot < pending) {
+      r.m[i] = p.lag_ml[((int64_t)c * 16 + m) * 2];
+      r.inv[i] = p.lag_ml[((int64_t)c * 16 + m) * 2 + 1];
+    }
+  }
+}
+
+// Weights the recorded calls give to the 32 rows of a slab whose first row has cache index `row_first`:
+// sum over calls and heads of 2^(s' - M') / L' for the rows a call saw.  sp[T] holds the logits of
+// tile T as the product left them.  On return lane l < 32 holds the weight of row l of the slab.
+__device__ __forceinline__ float record_weights(const floatx4_t (&sp)[2], const Record& r, float cs,
+                                                int row_first, int lane) {
+  const int n16 = lane & 15;
+  float w[2];
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc += fast_exp2(sp[T][i] * cs - r.m[i]) * r.inv[i];
+    // a row the call did not see is left out by a select: its logit may be anything
+    w[T] = (row_first + T * 16 + n16 < r.n_slot) ? acc : 0.f;
+    w[T] += __shfl_xor(w[T], 16);  // packed rows 4*jg .. 4*jg+3 sit in lane group jg
+    w[T] += __shfl_xor(w[T], 32);
+  }
+  return (lane & 16) ? w[1] : w[0];
+}
+
 #ifndef BAKLAVA_MFMA_WAVES_PER_EU
 #define BAKLAVA_MFMA_WAVES_PER_EU 2
 #endif
+template <bool LAG>
 __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode_partial_mfma(DecodeParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWaves * kSlab * kVStride];
-  // K staging; once a slab's A operands are read, the same bytes serve as the [head][row] buffer of
-  // the logit stash
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWaves * kSlab * kKStride];
-  // Score tracking, launches of one wave of workgroups: every wavefront keeps the logits of its slabs
-  // here ([G][32] floats per slab, p.stash_slots slabs) and writes them out when the work item is
-  // done (or the area is full), so that the stash writes of a launch fall together at its end
-  // instead of being interleaved with the K/V reads, which the memory system handles badly.
-  extern __shared__ __attribute__((aligned(16))) float lds_stash[];
-  static_assert(16 * kSlab * 4 <= kSlab * kKStride, "logit buffer fits the K staging area");
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWaves * kSlab * kKStride];  // K staging
+  // LAG: the new scores of the slabs a wavefront has processed ([32] floats per slab, p.ring_slots
+  // slabs per wavefront) wait here until the work item is done (or the area is full), so that the
+  // score writes of a launch fall together at its end instead of being interleaved with the K/V
+  // reads, which the memory system handles badly.
+  extern __shared__ __attribute__((aligned(16))) float lds_ring[];
 
   const Item it = p.items[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -78,9 +144,20 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   // Table entries are read before the fused append stores anything, so that they stay scalar loads.
   const int n_old = p.len[it.c];
   const int64_t off_c = it.row0 - it.start;
-  const int64_t stash0 = p.track ? p.stash_off[it.c] : 0;
-  const int n = n_old + p.fused_append;
-  if (p.fused_append) append_new_row(p, it, n_old, off_c);
+  // A fused append only happens while the cache has room; a full cache is attended as it is and
+  // reported through the status word.
+  const int add = (p.fused_append && n_old < p.cap[it.c]) ? 1 : 0;
+  const int n = n_old + add;
+  const int token_pos = p.token_pos_dev ? *p.token_pos_dev : p.token_pos;
+  // Recorded calls (LAG).  When the record is full this call adds their weights to the scores.
+  const int pending = LAG ? p.lag_cnt[(int64_t)it.c * G] : 0;
+  const bool apply = LAG && pending >= p.lag_batch;
+  Record rec;
+  if (LAG && apply) load_record(p, it.c, G, pending, n16, jg, rec);
+  if (p.fused_append) {
+    if (add) append_new_row(p, it, n_old, off_c, token_pos);
+    else if (it.start == 0 && threadIdx.x == 0) *p.status = 1;
+  }
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
   const int64_t row0 = off_c + it.start;
@@ -121,25 +198,24 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
     vr[i] = BAKLAVA_LD(reinterpret_cast<const u32x4_t*>(Vb + off));                               \
   }
 
-  // Logit stash (score tracking): a slab's logits form one contiguous block [G][32]; lane l < 8G
-  // stores 16 bytes of it, so every store instruction writes G whole, adjacent 128-byte lines.
-  // The pointer is formed once, before the loop: a load inside the loop would make the in-order
-  // wait counter stall on the prefetches.
-  float* lg = nullptr;
-  if (p.track && lane < 8 * G) lg = p.logits + (stash0 + (int64_t)it.start * G + lane * 4);
-  float* ring = lds_stash + wave * p.stash_slots * (kSlab * G);
+  // LAG: lane l < 32 owns row l of each slab.  The row's score is fetched with the slab's K rows;
+  // the new value goes to this wavefront's part of the LDS area and from there to HBM when the work
+  // item is done.
+  float* const sc_base = p.score + row0;
+  float sc_cur = 0.f;
+#define BAKLAVA_LOAD_SC(T0) \
+  if (LAG && apply && lane < kSlab) sc_cur = sc_base[min((T0) + lane, last)];
+  float* ring = lds_ring + wave * p.ring_slots * kSlab;
   int ring_n = 0;         // slabs held in the LDS area
   int ring_t0 = 0;        // first row of the oldest one; the others follow at kWaves * kSlab rows each
-  typedef float f32x4_t __attribute__((ext_vector_type(4)));
   auto flush_ring = [&]() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    for (int sidx = 0; sidx < ring_n; ++sidx) {
-      const float* src = ring + sidx * (kSlab * G) + lane * 4;
-      float* dst = lg + (ring_t0 + sidx * (kWaves * kSlab)) * G;
-      if (lg) *reinterpret_cast<f32x4_t*>(dst) = *reinterpret_cast<const f32x4_t*>(src);
-      if (lg && lane + 64 < 8 * G) *reinterpret_cast<f32x4_t*>(dst + 256) = *reinterpret_cast<const f32x4_t*>(src + 256);
+    // two slabs per store instruction: lanes 0..31 take an even slot, lanes 32..63 the next one
+    for (int sidx = lane >> 5; sidx < ring_n; sidx += 2) {
+      const int r = ring_t0 + sidx * (kWaves * kSlab) + (lane & 31);
+      if (r < cnt) sc_base[r] = ring[sidx * kSlab + (lane & 31)];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the area may be written again
@@ -152,6 +228,7 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   int t0 = wave * kSlab;
   if (t0 < cnt) {
     BAKLAVA_LOAD_K(t0)
+    BAKLAVA_LOAD_SC(t0)
   }
   // B operand of the first product: lane (g, j), chunk c holds Q[g][32c + 8j .. +8).
   bf16x8_t qb[4];
@@ -176,19 +253,26 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
       *reinterpret_cast<u32x4_t*>(myk + (jg + 4 * i) * kKStride + n16 * 16) = kr[i];
     }
     BAKLAVA_LOAD_K(tn)  // past the end every row clamps to the last live row: harmless re-reads
+    const float sc_old = sc_cur;
+    BAKLAVA_LOAD_SC(tn)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // ---- S^T = K Q^T: lane (row%16, j) reads elements 32c + 8j .. +8 of its row ----------------
-    floatx4_t s[2];
+    floatx4_t s[2], sp[2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
       s[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      sp[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const u32x4_t a = *reinterpret_cast<const u32x4_t*>(myk + (T * 16 + n16) * kKStride + c * 64 + jg * 16);
         s[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), qb[c], s[T], 0, 0, 0);
+        // The same K registers are a valid B operand (lane (row, j): elements 32c + 8j .. +8 of its
+        // row), so S' = Q' K^T costs no further LDS read: lane (row, jg) receives the pending
+        // call's logits of heads 4*jg .. 4*jg+3 for row 16T + row of the slab.
+        if (LAG && apply) sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
       }
     }
 
@@ -212,35 +296,11 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
         for (int i = 0; i < 4; ++i)
           if (t0 + T * 16 + jg * 4 + i >= cnt) x[T * 4 + i] = kNegInf;
     }
-    if (p.track && p.stash_slots > 0) {
-      // into the LDS area, in the layout of the global stash: one line of 32 rows per head
+    if (LAG && apply) {
+      const float wr = record_weights(sp, rec, cs, it.start + t0, lane);
       if (ring_n == 0) ring_t0 = t0;
-      float* tl = ring + ring_n * (kSlab * G);
-      if (n16 < G) {
-#pragma unroll
-        for (int T = 0; T < 2; ++T)
-          *reinterpret_cast<f32x4_t*>(tl + n16 * kSlab + T * 16 + jg * 4) =
-              f32x4_t{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
-      }
-      if (++ring_n == p.stash_slots) flush_ring();
-    } else if (p.track) {
-      // Through LDS from the accumulator layout (lane (g, jg): rows 4jg..4jg+3 of each tile) to
-      // one line per head.  Rows past the live length carry -inf and are never read back.
-      float* tl = reinterpret_cast<float*>(myk);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();  // the slab's K operands have been read
-      if (n16 < G) {
-#pragma unroll
-        for (int T = 0; T < 2; ++T)
-          *reinterpret_cast<f32x4_t*>(tl + n16 * kSlab + T * 16 + jg * 4) =
-              f32x4_t{x[T * 4], x[T * 4 + 1], x[T * 4 + 2], x[T * 4 + 3]};
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      if (lg) *reinterpret_cast<f32x4_t*>(lg + t0 * G) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4);
-      if (lg && lane + 64 < 8 * G)  // more than 8 query heads: the block has a second kilobyte
-        *reinterpret_cast<f32x4_t*>(lg + t0 * G + 256) = *reinterpret_cast<const f32x4_t*>(tl + lane * 4 + 256);
+      if (lane < kSlab) ring[ring_n * kSlab + lane] = sc_old + wr;  // lane l: row l of the slab
+      if (++ring_n == p.ring_slots) flush_ring();
     }
     float mx = x[0];
 #pragma unroll
@@ -290,8 +350,9 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
 #undef BAKLAVA_LD
 #undef BAKLAVA_LOAD_K
 #undef BAKLAVA_LOAD_V
+#undef BAKLAVA_LOAD_SC
 
-  if (ring_n > 0) flush_ring();
+  if (LAG && ring_n > 0) flush_ring();
 
   // Sum of the four lanes of a head.
   float l_tot = l_part;
@@ -318,17 +379,78 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   finish_item<kD, 16, kWaves>(p, it, G, n, sm_o, sm_m, sm_l);
 }
 
+// The recorded calls' weights without an attention call to ride on (baklava_flush_scores, and
+// baklava_compact before it ranks rows): a pass over the K rows alone.  Same work items, same
+// product and the same weights as in the attention kernel; K goes straight from HBM into the
+// operand layout (lane (row, j) reads elements 32c + 8j .. +8 of its row), one slab ahead.
+__global__ __launch_bounds__(64 * kWaves) void score_flush_mfma(DecodeParams p) {
+  const Item it = p.items[blockIdx.x];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n16 = lane & 15, jg = lane >> 4;
+  const int G = p.G;
+  const int pending = p.lag_cnt[(int64_t)it.c * G];
+  if (pending == 0) return;
+  int n_seen = 0;  // rows the latest recorded call saw: no earlier one saw more
+  for (int s = 0; s < 4; ++s)
+    if (s < pending) n_seen = max(n_seen, p.lag_n[(int64_t)it.c * 4 + s]);
+  const int cnt = min(it.start + it.count, n_seen) - it.start;
+  if (cnt <= 0) return;
+  Record rec;
+  load_record(p, it.c, G, pending, n16, jg, rec);
+  const int last = cnt - 1;
+  const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.k) + it.row0 * (kD * 2);
+  float* const sc_base = p.score + it.row0;
+  const float cs = p.scale_log2e;
+  u32x4_t a[2][4], an[2][4];
+  float sc_cur = 0.f, sc_next = 0.f;
+#define BAKLAVA_LOAD_SLAB(T0, dst, sc)                                                              \
+  _Pragma("unroll") for (int T = 0; T < 2; ++T) _Pragma("unroll") for (int c = 0; c < 4; ++c) {     \
+    const uint32_t off = (uint32_t)min((T0) + T * 16 + n16, last) * (kD * 2) + c * 64 + jg * 16;    \
+    dst[T][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off));             \
+  }                                                                                                 \
+  if (lane < kSlab) sc = sc_base[min((T0) + lane, last)];
+  int t0 = wave * kSlab;
+  if (t0 < cnt) {
+    BAKLAVA_LOAD_SLAB(t0, a, sc_cur)
+  }
+  for (; t0 < cnt; t0 += kWaves * kSlab) {
+    const int tn = t0 + kWaves * kSlab;
+    if (tn < cnt) {
+      BAKLAVA_LOAD_SLAB(tn, an, sc_next)
+    }
+    floatx4_t sp[2];
+#pragma unroll
+    for (int T = 0; T < 2; ++T) {
+      sp[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a[T][c]), sp[T], 0, 0, 0);
+    }
+    const float wr = record_weights(sp, rec, cs, it.start + t0, lane);
+    if (lane < kSlab && t0 + lane < cnt) sc_base[t0 + lane] = sc_cur + wr;
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) a[T][c] = an[T][c];
+    sc_cur = sc_next;
+  }
+#undef BAKLAVA_LOAD_SLAB
+}
+
 }  // namespace
 
-// Dynamic LDS the attention kernel may ask for: the whole LDS of a CU minus the static staging areas.
+// Dynamic LDS the attention kernel may ask for: the whole LDS of a CU minus the static staging areas
+// when a workgroup has the CU to itself, half of what two workgroups leave otherwise.
 constexpr int kLdsTotal = 160 * 1024;
 constexpr int kStatic = kWaves * kSlab * (kVStride + kKStride);
 constexpr int kDynMax = kLdsTotal - kStatic - 512;
+constexpr int kDynShared = (kLdsTotal - 2 * kStatic - 1024) / 2;
+static_assert(kDynShared >= kWaves * kSlab * 4, "room for one slab of scores per wavefront");
 
 // Called when a context is created on the current device, i.e. outside any stream capture: raises
 // the kernel's dynamic-LDS limit once, so that launches (captured or not) only launch.
 hipError_t prepare_decode_mfma() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma<true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, kDynMax);
 }
 
@@ -336,17 +458,26 @@ hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_cou
   if (n_items <= 0) return hipSuccess;
   if (p_in.G > 16) return hipErrorInvalidValue;
   DecodeParams p = p_in;
-  p.stash_slots = 0;
-  size_t dyn = 0;
-  if (p.track && one_wave) {
-    // the LDS left beside the staging areas, split over the wavefronts
-    const int slot_bytes = kSlab * p.G * 4;
-    const int fit = kDynMax / (kWaves * slot_bytes);
-    const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;  // slabs of the longest item per wavefront
-    p.stash_slots = std::max(1, std::min(fit, need));
-    dyn = (size_t)p.stash_slots * kWaves * slot_bytes;
+  p.ring_slots = 0;
+  if (!p.lag) {
+    decode_partial_mfma<false><<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
+    return hipGetLastError();
   }
-  decode_partial_mfma<<<dim3(n_items), dim3(64 * kWaves), dyn, s>>>(p);
+  // the LDS left beside the staging areas, split over the wavefronts; a launch of several waves of
+  // workgroups keeps room for two workgroups per compute unit
+  const int slot_bytes = kSlab * 4;
+  const int fit = (one_wave ? kDynMax : kDynShared) / (kWaves * slot_bytes);
+  const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;  // slabs of the longest item per wavefront
+  p.ring_slots = std::max(1, std::min(fit, need));
+  const size_t dyn = (size_t)p.ring_slots * kWaves * slot_bytes;
+  decode_partial_mfma<true><<<dim3(n_items), dim3(64 * kWaves), dyn, s>>>(p);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_flush_mfma(const DecodeParams& p, int n_items, hipStream_t s) {
+  if (n_items <= 0) return hipSuccess;
+  if (p.G > 16) return hipErrorInvalidValue;
+  score_flush_mfma<<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
   return hipGetLastError();
 }
 

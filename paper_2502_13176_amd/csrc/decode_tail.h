@@ -14,9 +14,10 @@ __device__ __forceinline__ float tail_exp2(float x) { return __builtin_amdgcn_ex
 
 // [K'; K_t], [V'; V_t] of Eq. 7 inside the attention kernel: the work item whose row range holds
 // slot `n_old` copies the new row there before it starts streaming.  The barrier makes the row
-// visible to every wavefront of this workgroup; no other workgroup reads that slot.
+// visible to every wavefront of this workgroup; no other workgroup reads that slot.  The caller
+// has checked n_old < capacity (uniform over the workgroup).
 __device__ __forceinline__ void append_new_row(const DecodeParams& p, const Item& it, int n_old,
-                                               int64_t off_c) {
+                                               int64_t off_c, int token_pos) {
   if (!(n_old >= it.start && n_old < it.start + it.count)) return;  // uniform over the workgroup
   const int tid = threadIdx.x;
   const int pieces = p.row_bytes / 16;
@@ -28,11 +29,17 @@ __device__ __forceinline__ void append_new_row(const DecodeParams& p, const Item
     char* dst = reinterpret_cast<char*>(plane ? p.v : p.k) + row * p.row_bytes + piece * 16;
     *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
   }
-  if (tid == 255) {
+  if (tid == (int)blockDim.x - 1) {
     p.score[row] = 0.f;
-    p.pos[row] = p.token_pos;
+    p.pos[row] = token_pos;
   }
   __syncthreads();
+}
+
+// Where a call's record goes: behind the pending ones, or to the front when this call has added
+// their weights to the scores (the record was full).
+__device__ __forceinline__ int lag_slot(const DecodeParams& p, int pending) {
+  return pending >= p.lag_batch ? 0 : pending;
 }
 
 // End of a work item.  On entry sm_o[w][g][d], sm_m[w][g], sm_l[w][g] (w < NW wavefronts, g-stride
@@ -67,6 +74,12 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
       if (d == 0) {
         p.final_ml[((int64_t)c * G + g) * 2 + 0] = ms;
         p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
+        if (p.lag) {
+          const int slot = lag_slot(p, p.lag_cnt[(int64_t)c * G + g]);
+          const int64_t m = (int64_t)c * 16 + (slot << p.lag_gp_log2) + g;
+          p.lag_ml[m * 2 + 0] = ms;
+          p.lag_ml[m * 2 + 1] = inv;
+        }
       }
     } else {
       p.part_o[((int64_t)it.slot * G + g) * D + d] = oo;
@@ -77,6 +90,22 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
     }
   }
   if (single && p.fused_append && tid == 0) p.len[c] = n_new;
+  if (single && p.lag) {
+    // The record a later pass over this cache needs to add this call's weights to the scores: the
+    // query rows (the normalisers went to lag_ml above), the number of rows they were taken over,
+    // and the new count of pending calls.  Every wavefront of this workgroup, the only one that
+    // serves the cache, has read the old record before the barriers that precede this function;
+    // the barrier below separates the last read of the old count from its update.
+    const int slot = lag_slot(p, p.lag_cnt[(int64_t)c * G]);
+    const int ppr = p.row_bytes / 16;  // 16-byte pieces per row
+    const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) + orow0 * p.row_bytes);
+    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<char*>(p.lag_q) +
+                                          ((int64_t)c * 16 + (slot << p.lag_gp_log2)) * p.row_bytes);
+    for (int i = tid; i < G * ppr; i += 64 * NW) dst[i] = src[i];
+    __syncthreads();
+    if (tid == 0) p.lag_n[(int64_t)c * 4 + slot] = n_new;
+    if (tid < G) p.lag_cnt[(int64_t)c * G + tid] = slot + 1;
+  }
 }
 
 }  // namespace baklava

@@ -63,8 +63,14 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
   const int G = p.G;
   const int n_old = p.len[it.c];
   const int64_t off_c = it.row0 - it.start;
-  const int n = n_old + p.fused_append;
-  if (p.fused_append) append_new_row(p, it, n_old, off_c);
+  // a fused append only happens while the cache has room (a full cache sets the status word)
+  const int add = (p.fused_append && n_old < p.cap[it.c]) ? 1 : 0;
+  const int n = n_old + add;
+  const int token_pos = p.token_pos_dev ? *p.token_pos_dev : p.token_pos;
+  if (p.fused_append) {
+    if (add) append_new_row(p, it, n_old, off_c, token_pos);
+    else if (it.start == 0 && threadIdx.x == 0) *p.status = 1;
+  }
   int cnt = min(it.start + it.count, n) - it.start;
   if (cnt < 0) cnt = 0;
   const int64_t row0 = off_c + it.start;
@@ -120,13 +126,6 @@ __global__ __launch_bounds__(256) void decode_partial_valu(DecodeParams p) {
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o);
         s[u][g] = live ? d : kNegInf;
-      }
-      if (p.track && live) {
-#pragma unroll
-        for (int g = 0; g < GT; ++g)
-          if (sub == g && g < G)
-            p.logits[p.stash_off[it.c] + (int64_t)((it.start + r) >> 5) * (32 * G) + 32 * g + ((it.start + r) & 31)] =
-                s[u][g];
       }
     }
 #pragma unroll
@@ -201,6 +200,8 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
   const int tid = threadIdx.x;
   const int d = tid % D, grp = tid / D;
   const int ib = mc.slot_begin, ie = mc.slot_end;
+  // where this call's record goes; read by every thread before the barrier below, written after it
+  const int slot = p.lag ? lag_slot(p, p.lag_cnt[(int64_t)c * G + g]) : 0;
   float m = kNegInf, l = 0.f, o = 0.f;
 #pragma unroll 8
   for (int s = ib + grp; s < ie; s += GROUPS) {
@@ -233,44 +234,91 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
     const float inv = 1.f / ll;
     const int c_rel = c - p.cache_begin;
     const int64_t orow = (int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G + g;
+    int n_now = 0;  // live rows after this call (thread 0 of head 0's block)
     p.out[orow * D + d] = oo * inv;
     if (d == 0) {
       p.final_ml[((int64_t)c * G + g) * 2 + 0] = ms;
       p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
-      if (g == 0 && p.fused_append) p.len[c] += 1;  // the fused append's row is now counted
+      if (g == 0) {
+        int n = p.len[c];
+        if (p.fused_append && n < p.cap[c]) p.len[c] = ++n;  // the fused append's row is now counted
+        n_now = n;
+      }
+    }
+    // This head's part of the record a later score pass over the cache needs (see DecodeParams).
+    // Each block reads and writes the pending-call counter of its own head only.
+    if (p.lag) {
+      const int64_t m = (int64_t)c * 16 + (slot << p.lag_gp_log2) + g;
+      if (tid * 16 < p.row_bytes) {
+        const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) + orow * p.row_bytes);
+        reinterpret_cast<uint4*>(reinterpret_cast<char*>(p.lag_q) + m * p.row_bytes)[tid] = src[tid];
+      }
+      if (d == 0) {
+        p.lag_ml[m * 2 + 0] = ms;
+        p.lag_ml[m * 2 + 1] = inv;
+        if (g == 0) p.lag_n[(int64_t)c * 4 + slot] = n_now;
+        p.lag_cnt[(int64_t)c * G + g] = slot + 1;
+      }
     }
   }
 }
 
-// score_j += sum_g 2^(s_gj - M_g) / L_g  (cumulative attention per cached token, summed over the
-// query heads that share the cache).  Workgroup (x, y) updates rows [y * kScoreTile, +kScoreTile)
-// of work item x, so that long work items still spread over many workgroups.
+// score_j += sum_g 2^(q_g . k_j scale - M_g) / L_g  (cumulative attention per cached token, summed
+// over the query heads that share the cache), from the K rows alone once the normalisers of the
+// call are final: the vector-ALU path's score update, launched right after its attention call.
+// Workgroup (x, y) updates rows [y * kScoreTile, +kScoreTile) of work item x, so that long work
+// items still spread over many workgroups.  Row layout as in the attention kernel above: a row
+// over D / EPL lanes, 64 / (D / EPL) rows per wavefront load.
 constexpr int kScoreTile = 1024;
-__global__ __launch_bounds__(256) void score_update_kernel(DecodeParams p) {
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(256) void score_pass_kernel(ScoreParams p) {
+  constexpr int EPL = Row<T>::EPL;
+  constexpr int LPR = D / EPL;
+  constexpr int RPW = 64 / LPR;
   const Item it = p.items[blockIdx.x];
   const int G = p.G;
-  const int n = p.len[it.c];
-  const int cnt = min(it.start + it.count, n) - it.start;
-  // Four consecutive rows per thread; work items start on a multiple of 64 rows, so the four
-  // logits of a head are one aligned 16-byte piece of the slab's [G][32] block.
-  const int r = blockIdx.y * kScoreTile + threadIdx.x * 4;
-  if (r >= cnt) return;
-  const int j = it.start + r;
-  const float* lg = p.logits + p.stash_off[it.c] + (int64_t)(j >> 5) * (32 * G) + (j & 31);
-  float w[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int g = 0; g < G; ++g) {
-    const float M = p.final_ml[((int64_t)it.c * G + g) * 2];
-    const float inv = p.final_ml[((int64_t)it.c * G + g) * 2 + 1];
-    const float4 x = *reinterpret_cast<const float4*>(lg + 32 * g);
-    w[0] += fast_exp2(x.x - M) * inv;
-    w[1] += fast_exp2(x.y - M) * inv;
-    w[2] += fast_exp2(x.z - M) * inv;
-    w[3] += fast_exp2(x.w - M) * inv;
-  }
-  float* sc = p.score + p.off[it.c] + j;
+  const int cnt = min(it.start + it.count, p.len[it.c]) - it.start;
+  const int r_begin = blockIdx.y * kScoreTile;
+  if (r_begin >= cnt) return;
+  const int r_end = min(cnt, r_begin + kScoreTile);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int c_rel = it.c - p.cache_begin;
+  const T* qrows = reinterpret_cast<const T*>(p.q) +
+                   ((int64_t)(c_rel / p.Hkv) * p.Hq + (int64_t)(c_rel % p.Hkv) * G) * D;
+  float qr[GT][EPL], M[GT], inv[GT];
 #pragma unroll
-  for (int e = 0; e < 4; ++e)
-    if (r + e < cnt) sc[e] += w[e];
+  for (int g = 0; g < GT; ++g) {
+    M[g] = 0.f;
+    inv[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qr[g][e] = 0.f;
+    if (g < G) {
+      Row<T>::widen(*reinterpret_cast<const uint4*>(qrows + g * D + sub * EPL), qr[g]);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qr[g][e] *= p.scale_log2e;
+      M[g] = p.ml[((int64_t)it.c * G + g) * 2];
+      inv[g] = p.ml[((int64_t)it.c * G + g) * 2 + 1];
+    }
+  }
+  const T* Kb = reinterpret_cast<const T*>(p.k) + it.row0 * D + sub * EPL;
+  float* sc = p.score + it.row0;
+  for (int r0 = r_begin + wave * RPW; r0 < r_end; r0 += 4 * RPW) {
+    const int r = r0 + rg;
+    float kf[EPL];
+    Row<T>::widen(load_nt16(Kb + (int64_t)min(r, r_end - 1) * D), kf);
+    float w = 0.f;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) d = fmaf(qr[g][e], kf[e], d);
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o);
+      w += fast_exp2(d - M[g]) * inv[g];  // heads beyond G: 2^0 * 0
+    }
+    if (r < r_end && sub == 0) sc[r] += w;
+  }
 }
 
 // [K'; K_t], [V'; V_t] of Eq. 7: the new row goes to slot len, then len += 1.
@@ -290,7 +338,7 @@ __global__ __launch_bounds__(64) void append_kernel(AppendParams p) {
   }
   if (lane == 63) {
     p.score[row] = 0.f;
-    p.pos[row] = p.token_pos;
+    p.pos[row] = p.token_pos_dev ? *p.token_pos_dev : p.token_pos;
   }
   __syncthreads();
   if (lane == 0) p.len[c] = n + 1;
@@ -331,10 +379,22 @@ hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_score_update(const DecodeParams& p, int n_items, int max_count, hipStream_t s) {
-  if (n_items <= 0 || max_count <= 0) return hipSuccess;
-  score_update_kernel<<<dim3(n_items, (max_count + kScoreTile - 1) / kScoreTile), dim3(256), 0, s>>>(p);
+template <typename T, int D>
+hipError_t launch_score_g(const ScoreParams& p, const dim3& grid, hipStream_t s) {
+  if (p.G <= 4) score_pass_kernel<T, D, 4><<<grid, dim3(256), 0, s>>>(p);
+  else if (p.G <= 8) score_pass_kernel<T, D, 8><<<grid, dim3(256), 0, s>>>(p);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_score_pass(const ScoreParams& p, int dtype, int D, int n_items, int max_count, hipStream_t s) {
+  if (n_items <= 0 || max_count <= 0) return hipSuccess;
+  const dim3 grid(n_items, (max_count + kScoreTile - 1) / kScoreTile);
+  if (dtype == 0 && D == 128) return launch_score_g<uint16_t, 128>(p, grid, s);
+  if (dtype == 0 && D == 64) return launch_score_g<uint16_t, 64>(p, grid, s);
+  if (dtype == 1 && D == 128) return launch_score_g<float, 128>(p, grid, s);
+  if (dtype == 1 && D == 64) return launch_score_g<float, 64>(p, grid, s);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s) {

@@ -30,6 +30,7 @@ extern "C" const char* baklava_strerror(int status) {
     case BAKLAVA_ECAPACITY: return "capacity exceeded";
     case BAKLAVA_EHIP: return "HIP runtime call failed";
     case BAKLAVA_ESTATE: return "call order violated";
+    case BAKLAVA_ENOMEM: return "host allocation failed";
     default: return "unknown status";
   }
 }

@@ -87,8 +87,12 @@ def fill_from_host(arena: B.Arena, w: synth.Workload, lens: Sequence[int], rng: 
     return st
 
 
-def download(arena: B.Arena, w: synth.Workload, caches: Optional[Sequence[int]] = None) -> HostState:
-    """Live rows of the given caches as the device holds them now."""
+def download(arena: B.Arena, w: synth.Workload, caches: Optional[Sequence[int]] = None, flush: bool = True) -> HostState:
+    """Live rows of the given caches as the device holds them now.  With score tracking the weights of
+    the latest attention call may still be owed to the score plane: baklava_flush_scores adds them first
+    (flush=False reads the plane as it stands)."""
+    if flush:
+        arena.flush_scores(0, arena.L)
     torch.cuda.synchronize()
     lens = arena.len.cpu().numpy()
     st = HostState(arena.n_caches)

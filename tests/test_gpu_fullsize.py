@@ -146,6 +146,7 @@ def test_cache_longer_than_the_longest_work_item():
 
     # one fused step (still two items): append, attention, score update over every row; the attention
     # calls above have added to the scores, so the step starts from the scores as they are now
+    arena.flush_scores(0, 2)
     torch.cuda.synchronize()
     for c in range(2):
         o = int(arena.off_host[c])

@@ -41,6 +41,7 @@ def test_decode_step_replays_from_a_graph(track, warm):
         with torch.cuda.stream(side):
             step()                                 # warm-up outside the capture
         torch.cuda.current_stream().wait_stream(side)
+    arena.flush_scores(0, w.L)                     # the warm-up's weights, before the plane is cleared
     torch.cuda.synchronize()
     arena.score.zero_()                            # the warm-up accumulated scores when tracking is on
     graph = torch.cuda.CUDAGraph()
@@ -62,6 +63,7 @@ def test_decode_step_replays_from_a_graph(track, warm):
         if track:
             # both the replay and the eager step added this step's attention: 2 * G per cache and step
             G = w.G
+            arena.flush_scores(0, w.L)             # the latest call's weights may still be owed
             sc = arena.score.cpu().numpy().astype(np.float64)
             for c in range(arena.n_caches):
                 o = int(arena.off_host[c])

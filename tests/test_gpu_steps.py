@@ -116,6 +116,92 @@ def test_multi_step_with_kernel_updated_scores(kernel, fused, base, Hq, Hkv, tar
     arena.close()
 
 
+# Score tracking adds a call's weights one call late (inside the next attention kernel) unless
+# baklava_flush_scores is called; the step-local test above flushes after every step, so the deferred
+# path gets a protocol of its own: the state is read back only at the start and the end of each window
+# of `interval` steps; inside a window the calls follow each other as a model issues them.
+LAG_CASES = [("long", 8, 2, 2, 0, True), ("long", 8, 2, 2, 3, False), ("qwen", 7, 1, 2, 0, True),
+             ("long", 16, 1, 2, 1, True), ("long", 16, 8, 9, -1, True), ("long", 4, 4, 3, 2, False)]
+
+
+@pytest.mark.parametrize("base,Hq,Hkv,batch,target,fused", LAG_CASES)
+def test_deferred_score_updates_over_windows_of_steps(base, Hq, Hkv, batch, target, fused):
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS[base], name="lag", L=2, Hq=Hq, Hkv=Hkv, batch=batch, ctx=2048, lo=96,
+                     hi=2048, interval=6, slack=6, sink=4, recent=16, steps=18 if batch < 9 else 12, floor_frac=0.0,
+                     seed=77 + Hq)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    arena = H.make_arena(w, budgets, track=True)
+    arena.set_option(B.OPT_KERNEL, B.KERNEL_MFMA)
+    if target >= 0:
+        H.set_chunk(arena, 256)
+        arena.set_option(B.OPT_TARGET_ITEMS, target)
+        arena.set_option(B.OPT_TARGET_ITEMS_WHOLE, target)
+    cpl = w.batch * w.Hkv
+    lens = [budgets[(c // cpl) * w.Hkv + c % w.Hkv] - (c % 3) for c in range(arena.n_caches)]
+    H.fill_from_host(arena, w, lens, rng, scores="uniform")
+    dev = arena.device
+    worst_out = worst_score = 0.0
+    for t0 in range(0, w.steps, w.interval):
+        start = H.download(arena, w)                       # brings the scores up to date first
+        caches = [H.oracle_cache(w, start, c) for c in range(arena.n_caches)]
+        for t in range(t0 + 1, t0 + w.interval + 1):
+            q, q64 = H.make_q(w, rng, w.L)
+            knew = synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype)
+            vnew = synth.payload(rng, (w.L, w.batch, w.Hkv, w.D), w.dtype)
+            kd, vd, qd = (H.to_device_storage(a, w.dtype, dev) for a in (knew, vnew, q))
+            outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+            whole = t % 3 == 0                             # both launch shapes inside one window
+            if fused and whole:
+                arena.append_decode_attn(0, w.L, kd, vd, 5000 + t, qd, outd)
+            elif fused:
+                for l in range(w.L):
+                    arena.append_decode_attn(l, 1, kd[l], vd[l], 5000 + t, qd[l], outd[l])
+            else:
+                arena.append(0, w.L, kd, vd, 5000 + t)
+                if whole:
+                    arena.decode_attn(0, w.L, qd, outd)
+                else:
+                    for l in range(w.L):
+                        arena.decode_attn(l, 1, qd[l], outd[l])
+            torch.cuda.synchronize()
+            out = outd.cpu().numpy().astype(np.float64)
+            k64, v64 = synth.storage_to_f64(knew, w.dtype), synth.storage_to_f64(vnew, w.dtype)
+            for c in range(arena.n_caches):
+                l, b, hs = H.q_rows_of_cache(w, c)
+                ref, _, _ = O.decode_step(caches[c], q64[l, b, hs], k64[l, b, c % w.Hkv], v64[l, b, c % w.Hkv], 5000 + t, t,
+                                          budget=0, sink=0, recent=0, interval=0, track_scores=True)
+                err = float(np.max(np.abs(out[l, b, hs] - ref)))
+                assert err <= H.ATTN_TOL, f"step {t} cache {c}: attention error {err:.3e}"
+                worst_out = max(worst_out, err)
+        # without a flush the plane lacks the weights of the calls still on record, and only those: a record
+        # holds 16 / (G rounded up to 4, 8 or 16) calls, at most 4, and the call that finds it full empties it
+        room = min(4, 16 // (4 if w.G <= 4 else 8 if w.G <= 8 else 16))
+        on_record = 0
+        for _ in range(w.interval):
+            on_record = 1 if on_record >= room else on_record + 1
+        raw = H.download(arena, w, flush=False)
+        post = H.download(arena, w)
+        for c in range(arena.n_caches):
+            oc = caches[c]
+            assert post.K[c].shape[0] == oc.n and np.array_equal(post.pos[c], oc.pos[:oc.n])
+            serr = np.abs(post.score[c].astype(np.float64) - oc.score[:oc.n])
+            assert np.all((serr <= SCORE_TOL) | (serr <= SCORE_TOL * np.abs(oc.score[:oc.n]))), \
+                f"window ending at step {t0 + w.interval}, cache {c}: score error {serr.max():.3e}"
+            worst_score = max(worst_score, float(serr.max()))
+            owed = post.score[c].astype(np.float64).sum() - raw.score[c].astype(np.float64).sum()
+            assert abs(owed - on_record * w.G) <= 1e-3, \
+                f"cache {c}: the unflushed plane lacks {owed:.6f}, not the weights of {on_record} calls"
+        kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev)
+        arena.compact(0, w.L, kept_dev)
+        torch.cuda.synchronize()
+        H.check_eviction_against_oracle(arena, w, budgets, post, H.download(arena, w), kept_dev, range(arena.n_caches))
+        assert arena.lengths().tolist() == arena.len.cpu().tolist()
+    print(f"deferred scores G={w.G}: worst attention error {worst_out:.3e}, worst score error {worst_score:.3e}", flush=True)
+    arena.close()
+
+
 def test_scores_sum_to_G_per_step_without_eviction():
     """Each query head's softmax weights sum to 1, so a cache's scores grow by exactly G per step."""
     H = _h()

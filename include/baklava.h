@@ -182,8 +182,11 @@ enum {
                                    Default: the device's number of compute units (one wave of
                                    workgroups) while a layer holds at most a quarter as many caches,
                                    otherwise five times that number, with a shortest run of 256 rows */
-  BAKLAVA_OPT_TARGET_ITEMS_WHOLE = 6 /* the same for launches over all layers at once.  Default: five
+  BAKLAVA_OPT_TARGET_ITEMS_WHOLE = 6, /* the same for launches over all layers at once.  Default: five
                                    times the device's number of compute units                      */
+  BAKLAVA_OPT_TRACK_SCORES = 7  /* 0: attention calls stop adding to the scores (calls already on
+                                   record stay there until the next flush); 1: they resume.  Only a
+                                   context created with track_scores can be switched to 1          */
 };
 int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
 

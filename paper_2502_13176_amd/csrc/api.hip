@@ -142,6 +142,7 @@ struct baklava_ctx {
   WorkspacePlan plan;
   char* ws;
   bool time_kernel;
+  bool track_on;               // score tracking in force (BAKLAVA_OPT_TRACK_SCORES pauses it)
   std::vector<hipEvent_t> ev;  // pairs (before, after); the first 2 * ev_used are recorded
   size_t ev_used;
 };
@@ -262,7 +263,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   hipStream_t s = (hipStream_t)stream;
   const bool mfma_able = ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128;
   const bool use_mfma = ctx->kernel_pref == 2 || (ctx->kernel_pref == 0 && mfma_able);
-  const bool track = ctx->d.track_scores != 0;
+  const bool track = ctx->track_on;
   // The vector-ALU kernel adds its weights right after the call; weights an earlier MFMA call left
   // pending come first, so that the scores grow in the order of the calls.
   if (track && !use_mfma) {
@@ -403,6 +404,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
     ctx->target_items_whole = kWholeItemsPerCu * cus;
   }
   ctx->time_kernel = false;
+  ctx->track_on = desc->track_scores != 0;
   ctx->ev_used = 0;
   ctx->plan = plan_workspace(desc, cap_host, budget_host);
   ctx->ws = reinterpret_cast<char*>(desc->workspace);
@@ -495,6 +497,11 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       if (value == 2 && !(ctx->d.dtype == BAKLAVA_BF16 && ctx->d.D == 128)) return BAKLAVA_EINVAL;
       if (value == 1 && ctx->G > 8) return BAKLAVA_EINVAL;
       ctx->kernel_pref = (int32_t)value;
+      return BAKLAVA_OK;
+    case BAKLAVA_OPT_TRACK_SCORES:
+      if (value != 0 && value != 1) return BAKLAVA_EINVAL;
+      if (value == 1 && !ctx->d.track_scores) return BAKLAVA_EINVAL;  // the workspace holds no records
+      ctx->track_on = value == 1;
       return BAKLAVA_OK;
     case BAKLAVA_OPT_TIME_KERNEL:
       if (value != 0 && value != 1) return BAKLAVA_EINVAL;

@@ -40,6 +40,7 @@
 #include "decode_tail.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace baklava {
 
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
   float* const sc_base = p.score + row0;
   float sc_cur = 0.f;
 #define BAKLAVA_LOAD_SC(T0) \
-  if (LAG && apply && lane < kSlab) sc_cur = sc_base[min((T0) + lane, last)];
+  if (APPLY && lane < kSlab) sc_cur = sc_base[min((T0) + lane, last)];
   float* ring = lds_ring + wave * p.ring_slots * kSlab;
   int ring_n = 0;         // slabs held in the LDS area
   int ring_t0 = 0;        // first row of the oldest one; the others follow at kWaves * kSlab rows each
@@ -222,6 +223,10 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
     ring_n = 0;
   };
 
+  // The stream over the work item's rows, compiled twice: with the score update of the recorded
+  // calls (APPLY) and without it, so that calls that only record run the plain loop.
+  auto stream_rows = [&](auto apply_tag) {
+  constexpr bool APPLY = decltype(apply_tag)::value;
   // Order of the first loads: K of the first slab, then the query, then V.  The loop's first wait
   // (for K and, on the first pass, the query) then leaves the V loads in flight, and the stream
   // starts one memory round trip earlier than with the query fetched first.
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
         // The same K registers are a valid B operand (lane (row, j): elements 32c + 8j .. +8 of its
         // row), so S' = Q' K^T costs no further LDS read: lane (row, jg) receives the pending
         // call's logits of heads 4*jg .. 4*jg+3 for row 16T + row of the slab.
-        if (LAG && apply) sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
+        if (APPLY) sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
       }
     }
 
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
         for (int i = 0; i < 4; ++i)
           if (t0 + T * 16 + jg * 4 + i >= cnt) x[T * 4 + i] = kNegInf;
     }
-    if (LAG && apply) {
+    if (APPLY) {
       const float wr = record_weights(sp, rec, cs, it.start + t0, lane);
       if (ring_n == 0) ring_t0 = t0;
       if (lane < kSlab) ring[ring_n * kSlab + lane] = sc_old + wr;  // lane l: row l of the slab
@@ -347,12 +352,14 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
+  if (APPLY && ring_n > 0) flush_ring();
+  };  // stream_rows
+  if (LAG && apply) stream_rows(std::true_type{});
+  else stream_rows(std::false_type{});
 #undef BAKLAVA_LD
 #undef BAKLAVA_LOAD_K
 #undef BAKLAVA_LOAD_V
 #undef BAKLAVA_LOAD_SC
-
-  if (LAG && ring_n > 0) flush_ring();
 
   // Sum of the four lanes of a head.
   float l_tot = l_part;

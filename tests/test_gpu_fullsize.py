@@ -23,6 +23,27 @@ def sample_caches(arena, lens, rng, n_random=10):
     return sorted(picks)
 
 
+def short_caches(lens, limit=4096, at_most=400):
+    """Caches of at most `limit` rows, evenly thinned to `at_most` of them: cheap enough to check one by
+    one, so evictions are compared on hundreds of caches rather than on a handful."""
+    ids = [c for c in range(len(lens)) if lens[c] <= limit]
+    stride = max(1, -(-len(ids) // at_most))
+    return ids[::stride]
+
+
+def check_evictions(H, arena, w, budgets, pre, post, kept_dev, caches, lens):
+    cpl = w.batch * w.Hkv
+    for c in caches:
+        b = budgets[(c // cpl) * w.Hkv + c % w.Hkv]
+        kept = O.compact_select(pre.score[c], int(lens[c]), b, w.sink, w.recent)
+        o = int(arena.off_host[c])
+        got = kept_dev[o:o + len(kept)].cpu().numpy()
+        assert np.array_equal(got, np.asarray(kept, dtype=np.int32)), f"cache {c}: kept list"
+        assert np.array_equal(post.K[c], pre.K[c][kept]) and np.array_equal(post.V[c], pre.V[c][kept])
+        assert np.array_equal(post.score[c].view(np.uint32), pre.score[c][kept].view(np.uint32))
+        assert np.array_equal(post.pos[c], pre.pos[c][kept])
+
+
 @pytest.mark.parametrize("name", ["llama32", "qwen", "long"])
 def test_full_size_decode_and_compaction(name):
     H = _h()
@@ -51,7 +72,8 @@ def test_full_size_decode_and_compaction(name):
     assert float((out_layer - out_stack).abs().max()) <= 1e-5
 
     picks = sample_caches(arena, lens, rng)
-    pre = H.download(arena, w, picks)
+    many = sorted(set(picks) | set(short_caches(lens)))      # evictions: these as well
+    pre = H.download(arena, w, many)
     q64 = synth.storage_to_f64(H.from_device_storage(q, w.dtype), w.dtype)
     ol = out_layer.cpu().numpy().astype(np.float64)
     worst = H.check_decode_against_oracle(arena, w, pre, q64, ol, caches=picks)
@@ -65,15 +87,9 @@ def test_full_size_decode_and_compaction(name):
     new_len = arena.len.cpu().numpy()
     want = np.minimum(lens, np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]))
     assert np.array_equal(new_len, want) and np.array_equal(arena.lengths(), want)
-    post = H.download(arena, w, picks)
-    for c in picks:
-        b = budgets[(c // cpl) * w.Hkv + c % w.Hkv]
-        kept = O.compact_select(pre.score[c], int(lens[c]), b, w.sink, w.recent)
-        o = int(arena.off_host[c])
-        got = kept_dev[o:o + len(kept)].cpu().numpy()
-        assert np.array_equal(got, np.asarray(kept, dtype=np.int32)), f"cache {c}: kept list"
-        assert np.array_equal(post.K[c], pre.K[c][kept]) and np.array_equal(post.V[c], pre.V[c][kept])
-        assert np.array_equal(post.score[c], pre.score[c][kept]) and np.array_equal(post.pos[c], pre.pos[c][kept])
+    post = H.download(arena, w, many)
+    check_evictions(H, arena, w, budgets, pre, post, kept_dev, many, lens)
+    print(f"{name}: eviction lists and moved rows bit-exact on {len(many)} caches", flush=True)
     # any size: every kept list is strictly ascending and starts with the sink rows
     for c in sample_caches(arena, lens, rng, 40):
         o, n = int(arena.off_host[c]), int(new_len[c])
@@ -84,6 +100,79 @@ def test_full_size_decode_and_compaction(name):
     arena.decode_attn(0, w.L, q, out_stack)
     torch.cuda.synchronize()
     H.check_decode_against_oracle(arena, w, post, q64, out_stack.cpu().numpy().astype(np.float64), caches=picks)
+    arena.close()
+    del arena
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["llama32", "qwen"])
+def test_tracked_decode_loop_at_full_size(name):
+    """The decode loop as bench.py times it (one fused launch per layer, attention weights accumulated
+    per row, eviction every 64 steps) at full size for 65 steps.  Steps 1, 64 and 65 are checked
+    step-locally on sampled caches; between steps 1 and 63 nothing is flushed, so the scores grow
+    through the attention kernel's deferred updates alone, and at step 63 they must match an oracle that
+    ran the same 62 steps on its own; the eviction after step 64 is compared bit for bit on the sampled
+    caches and on hundreds of short ones."""
+    H = _h()
+    w = synth.WORKLOADS[name]
+    rng = np.random.Generator(np.random.PCG64(w.seed + 23))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    arena = H.make_arena(w, budgets, track=True)
+    gen = synth.fill_arena_on_device(arena, w)          # K, V ~ N(0,1), scores U(0,1), pos = row index
+    cpl = w.batch * w.Hkv
+    bud_of = np.array([budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)], dtype=np.int32)
+    arena.set_lengths(bud_of)
+    dev = arena.device
+    picks = sample_caches(arena, bud_of, rng, n_random=6)
+    order = np.argsort(bud_of)
+    runners = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2])} | {int(x) for x in rng.integers(0, arena.n_caches, 4)})
+    shape_q, shape_kv = (w.L, w.batch, w.Hq, w.D), (w.L, w.batch, w.Hkv, w.D)
+    out = torch.zeros(shape_q, dtype=torch.float32, device=dev)
+    free = {}                                           # cache -> oracle cache that runs steps 2..63 on its own
+    for t in range(1, 66):
+        q = torch.randn(shape_q, generator=gen, device=dev).to(torch.bfloat16)
+        kn = torch.randn(shape_kv, generator=gen, device=dev).to(torch.bfloat16)
+        vn = torch.randn(shape_kv, generator=gen, device=dev).to(torch.bfloat16)
+        local = t in (1, 64, 65)
+        pre = H.download(arena, w, sorted(set(picks) | set(runners))) if local else None
+        if t == 64:
+            for c in runners:                           # 62 steps of deferred updates against the oracle's own run
+                oc = free[c]
+                serr = np.abs(pre.score[c].astype(np.float64) - oc.score)
+                assert pre.K[c].shape[0] == oc.n and np.array_equal(pre.pos[c], oc.pos)
+                assert np.all((serr <= 2e-3) | (serr <= 2e-3 * np.abs(oc.score))), f"cache {c}: scores after 63 steps, {serr.max():.3e}"
+            print(f"{name}, step 63: scores of {len(runners)} caches match the oracle's own 62-step run", flush=True)
+        for l in range(w.L):
+            arena.append_decode_attn(l, 1, kn[l], vn[l], w.ctx + t, q[l], out[l])
+        torch.cuda.synchronize()
+        q64 = synth.storage_to_f64(H.from_device_storage(q, "bf16"), "bf16")
+        k64 = synth.storage_to_f64(H.from_device_storage(kn, "bf16"), "bf16")
+        v64 = synth.storage_to_f64(H.from_device_storage(vn, "bf16"), "bf16")
+        got = out.cpu().numpy().astype(np.float64)
+        if local:
+            post = H.download(arena, w, sorted(set(picks) | set(runners)))
+            e = H.check_step_against_oracle(arena, w, pre, post, got, q64, k64, v64, w.ctx + t, t, picks)
+            print(f"{name}, step {t}: {len(picks)} sampled caches, worst attention error {e[0]:.3e}, "
+                  f"worst score error {e[1]:.3e}", flush=True)
+            if t == 1:
+                free = {c: H.oracle_cache(w, post, c) for c in runners}
+        elif t <= 63:
+            for c in runners:
+                l, b, hs = H.q_rows_of_cache(w, c)
+                ref, _, _ = O.decode_step(free[c], q64[l, b, hs], k64[l, b, c % w.Hkv], v64[l, b, c % w.Hkv], w.ctx + t, t,
+                                          budget=0, sink=0, recent=0, interval=0, track_scores=True)
+                err = float(np.max(np.abs(got[l, b, hs] - ref)))
+                assert err <= H.ATTN_TOL, f"step {t} cache {c}: attention error {err:.3e}"
+        if t == 64:
+            lens = arena.lengths()
+            many = sorted(set(picks) | set(short_caches(lens)))
+            before = H.download(arena, w, many)
+            kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=dev)
+            arena.compact(0, w.L, kept_dev)
+            torch.cuda.synchronize()
+            check_evictions(H, arena, w, budgets, before, H.download(arena, w, many), kept_dev, many, lens)
+            assert np.array_equal(arena.lengths(), bud_of) and np.array_equal(arena.len.cpu().numpy(), bud_of)
+            print(f"{name}: eviction after step 64 bit-exact on {len(many)} caches", flush=True)
     arena.close()
     del arena
     torch.cuda.empty_cache()

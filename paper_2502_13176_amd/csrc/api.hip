@@ -40,8 +40,8 @@ struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
   size_t items[2], multi[2];
   size_t part_o, part_ml, final_ml, lag_q, lag_ml, lag_n, lag_cnt, status, kept, info, order_all, order_layer;
-  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, total;
-  int64_t n_segs, halo_rows;
+  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, tiles, tile_hist, sel_state, tile_base_cnt, long_first, total;
+  int64_t n_segs, halo_rows, n_tiles, n_long;
   int64_t max_items;
 };
 
@@ -111,6 +111,19 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   w.halo_v = o;       o = align256(o + (size_t)w.halo_rows * row_bytes);
   w.halo_score = o;   o = align256(o + (size_t)w.halo_rows * 4);
   w.halo_pos = o;     o = align256(o + (size_t)w.halo_rows * 4);
+  // selection of the caches too long for one workgroup: tile table and per-tile digit counters
+  w.n_tiles = 0;
+  w.n_long = 0;
+  for (int64_t c = 0; c < n_caches; ++c)
+    if (cap[c] > kLongRows) {
+      w.n_tiles += ((int64_t)cap[c] + kTileRows - 1) / kTileRows;
+      w.n_long += 1;
+    }
+  w.tiles = o;        o = align256(o + (size_t)w.n_tiles * sizeof(SelTile));
+  w.tile_hist = o;    o = align256(o + (size_t)w.n_tiles * 4 * 256 * 4);
+  w.sel_state = o;    o = align256(o + (size_t)w.n_tiles * sizeof(SelState));
+  w.tile_base_cnt = o; o = align256(o + (size_t)w.n_tiles * 2 * 4);
+  w.long_first = o;   o = align256(o + (size_t)w.n_long * 4);
   w.total = o;
   return w;
 }
@@ -127,6 +140,8 @@ struct baklava_ctx {
   std::vector<int32_t> cap, len, budget;
   std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
   std::vector<int32_t> seg_begin;               // cache -> first segment of the eviction move
+  std::vector<int32_t> tile_begin;              // cache -> first tile of the tiled selection (long caches only have any)
+  std::vector<int32_t> long_begin;              // cache -> number of long caches before it
   int32_t kernel_pref;
   bool layer_one_wave;   // default schedule of layer-range launches: one workgroup per compute unit
   int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
@@ -215,7 +230,9 @@ int flush_records(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, hi
   p.lag_cnt = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.lag_cnt);
   p.G = ctx->G; p.lag_gp_log2 = ctx->lag_gp_log2;
   p.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)ctx->d.D));
-  if (!hip_ok(launch_score_flush_mfma(p, i1 - i0, s))) return BAKLAVA_EHIP;
+  const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
+                                            sc.max_count.begin() + layer_begin + layer_count);
+  if (!hip_ok(launch_score_flush_mfma(p, i1 - i0, longest, s))) return BAKLAVA_EHIP;
   if (!hip_ok(launch_fill_i32(p.lag_cnt + c0 * ctx->G, 0, (c1 - c0) * ctx->G, s))) return BAKLAVA_EHIP;
   return BAKLAVA_OK;
 }
@@ -458,6 +475,33 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       return BAKLAVA_EHIP;
     }
   }
+  // Tile table of the selection for long caches (depends on capacities only), in cache order, so that
+  // the tiles of a layer range are a contiguous slice.
+  {
+    std::vector<SelTile> tiles;
+    std::vector<int32_t> long_first;
+    tiles.reserve((size_t)ctx->plan.n_tiles);
+    ctx->tile_begin.assign(n_caches + 1, 0);
+    ctx->long_begin.assign(n_caches + 1, 0);
+    for (int64_t c = 0; c < n_caches; ++c) {
+      ctx->tile_begin[c] = (int32_t)tiles.size();
+      ctx->long_begin[c] = (int32_t)long_first.size();
+      if (ctx->cap[c] <= kLongRows) continue;
+      const int32_t nt = (int32_t)(((int64_t)ctx->cap[c] + kTileRows - 1) / kTileRows);
+      const int32_t first = (int32_t)tiles.size();
+      long_first.push_back(first);
+      for (int32_t t = 0; t < nt; ++t) tiles.push_back(SelTile{(int32_t)c, t, first, nt});
+    }
+    ctx->tile_begin[n_caches] = (int32_t)tiles.size();
+    ctx->long_begin[n_caches] = (int32_t)long_first.size();
+    if ((int64_t)tiles.size() != ctx->plan.n_tiles || (int64_t)long_first.size() != ctx->plan.n_long ||
+        (!tiles.empty() &&
+         (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.tiles, tiles.data(), tiles.size() * sizeof(SelTile), hipMemcpyHostToDevice)) ||
+          !hip_ok(hipMemcpy(ctx->ws + ctx->plan.long_first, long_first.data(), long_first.size() * 4, hipMemcpyHostToDevice))))) {
+      delete ctx;
+      return BAKLAVA_EHIP;
+    }
+  }
   if (!hip_ok(prepare_decode_mfma())) { delete ctx; return BAKLAVA_EHIP; }
   int st = build_schedule(ctx, 0, ctx->layer_one_wave ? kDefaultChunk : kDefaultChunkWhole);
   if (st == BAKLAVA_OK) st = build_schedule(ctx, 1, kDefaultChunkWhole);
@@ -651,7 +695,16 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
     const int st = flush_records(ctx, layer_begin, layer_count, s);
     if (st != BAKLAVA_OK) return st;
   }
-  if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), s))) return BAKLAVA_EHIP;
+  p.cap = ctx->d.cap;
+  const int32_t t0 = ctx->tile_begin[c0], t1 = ctx->tile_begin[c1];
+  p.tiles = reinterpret_cast<const SelTile*>(ctx->ws + ctx->plan.tiles) + t0;
+  p.tile_hist = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.tile_hist);
+  p.sel_state = reinterpret_cast<SelState*>(ctx->ws + ctx->plan.sel_state);
+  p.tile_base_cnt = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.tile_base_cnt);
+  const int32_t l0 = ctx->long_begin[c0], l1 = ctx->long_begin[c1];
+  p.long_first = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.long_first) + l0;
+  p.tile_base = t0;
+  if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), t1 - t0, l1 - l0, s))) return BAKLAVA_EHIP;
   if (!hip_ok(launch_compact_move(p, s1 - s0, s))) return BAKLAVA_EHIP;
   for (int64_t c = c0; c < c1; ++c) {
     const int32_t b = ctx->budget[(c / ctx->cpl) * ctx->d.Hkv + c % ctx->d.Hkv];

@@ -1,5 +1,6 @@
 // Budget-enforcing eviction (f_evict, Eqs. 5-6): selection of the surviving rows (one workgroup
-// per cache, long caches first), then a stable in-place move (one workgroup per segment).
+// per cache, long caches first; caches beyond what one workgroup sweeps quickly are cut into tiles
+// and go through one kernel per radix pass), then a stable in-place move (one workgroup per segment).
 #include "common.h"
 
 namespace baklava {
@@ -9,7 +10,8 @@ namespace {
 constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelUnroll = 8;  // score loads in flight per thread in the counting passes
-constexpr int kSelRows = 4;    // consecutive rows per thread in the emit pass
+constexpr int kSelRows = 16;   // consecutive rows per thread in the emit pass (four 16-byte loads)
+constexpr int kEmitTile = kSelThreads * kSelRows;
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key); -0 is folded onto +0 so
 // that it ties with it, as a floating-point comparison would.
@@ -42,71 +44,186 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* sm, int& total) 
   return base + incl - v;
 }
 
+// What the selection of one cache is after: the middle rows [mid_lo, mid_hi) compete for k places.
+struct SelGoal {
+  int n, b, k, mid_lo, mid_hi;
+};
+
+__device__ __forceinline__ SelGoal sel_goal(const CompactParams& p, int c) {
+  SelGoal g;
+  g.n = p.len[c];
+  const int cpl = p.batch * p.Hkv;
+  g.b = p.budget[(c / cpl) * p.Hkv + c % p.Hkv];
+  const int s = p.sink;
+  const int r = (p.policy == 1) ? (g.b - s) : p.recent;
+  g.k = g.b - s - r;  // middle rows that survive, >= 0 (checked at context creation)
+  g.mid_lo = s;
+  g.mid_hi = g.n - r;
+  return g;
+}
+
+// One counting pass of the radix select over rows [j_begin, j_end) of the middle: keys whose digits
+// above `shift` equal `prefix` are counted by their digit at `shift` into the LDS histogram.
+// A thread adds up runs of equal digits among its own keys before it touches the histogram: in
+// the first pass most scores share their leading bits, and one atomic per key on the same few
+// counters would serialise the whole workgroup.
+template <int UNROLL>
+__device__ __forceinline__ void count_digits(const float* score, int j_begin, int j_end, uint32_t prefix,
+                                             uint32_t mask, int shift, int* hist) {
+  const int tid = threadIdx.x;
+  for (int j0 = j_begin + tid; j0 < j_end; j0 += kSelThreads * UNROLL) {
+    uint32_t key[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int j = j0 + u * kSelThreads;
+      key[u] = score_key(j < j_end ? score[j] : 0.f);
+    }
+    int run_digit = -1, run = 0;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int j = j0 + u * kSelThreads;
+      const bool live = j < j_end && (key[u] & mask) == prefix;
+      const int digit = (key[u] >> shift) & 255;
+      if (live && digit == run_digit) {
+        run += 1;
+      } else if (live) {
+        if (run) atomicAdd(&hist[run_digit], run);
+        run_digit = digit;
+        run = 1;
+      }
+    }
+    if (run) atomicAdd(&hist[run_digit], run);
+  }
+}
+
+// The digit of the need-th largest key given the 256 counters of a pass: thread t looks at digit
+// 255 - t; `above` = keys with a larger digit.  Exactly one digit has above < need <= above + its own
+// count.  Results through the shared words; ends with a barrier.
+__device__ __forceinline__ void find_digit(const int* hist, int need, int* sm_scan, int* sh_digit, int* sh_need) {
+  const int tid = threadIdx.x;
+  const int mine = tid < 256 ? hist[255 - tid] : 0;
+  int all;
+  const int above = block_exclusive_scan(mine, sm_scan, all);
+  if (tid < 256 && above < need && above + mine >= need) {
+    *sh_digit = 255 - tid;
+    *sh_need = need - above;
+  }
+  __syncthreads();
+}
+
+// LDS an emit needs: the keys of a tile, padded by one word per 16 so that a thread's 16 consecutive
+// keys and its neighbours' fall into different banks, and the tile's part of the kept list.
+constexpr int kEmitKeyWords = kEmitTile + kEmitTile / 16;
+
+// Stable emit of the rows [j_begin, j_end) of a cache.  A row survives if it is a sink or recent
+// row, if its key exceeds the threshold, or if it is among the first need_eq rows (of the whole
+// cache) whose key equals it; its place in the list is the number of survivors before it, i.e.
+// (rows of the first two kinds before it) + min(rows with an equal key before it, need_eq).  Both
+// counts come from one workgroup scan of a packed pair per tile of kEmitTile rows (at most
+// kSelRows * kSelThreads = 2^13 each).  sure_base / eq_base: the two counts over the rows before
+// j_begin.  Global memory is touched in whole lines only: the tile's scores are loaded row t,
+// t + 512, ... per thread (all loads in flight at once) and handed to the thread that owns 16
+// consecutive rows through LDS; the tile's survivors, which occupy consecutive places of the list,
+// are collected in LDS and written out together.  The smallest evicted row index of the range goes
+// to *sh_first (shared, initialised by the caller to the cache's length).
+__device__ __forceinline__ void emit_rows(const float* score, int32_t* kept, const SelGoal& g, uint32_t thr,
+                                          int need_eq, int j_begin, int j_end, int sure_base, int eq_base,
+                                          int* sm_scan, int* sh_first, uint32_t* lds_key, int32_t* lds_out) {
+  const int tid = threadIdx.x;
+  const int n = g.n;
+  for (int j0 = j_begin; j0 < j_end; j0 += kEmitTile) {
+    if (g.k > 0) {
+      float sc[kSelRows];
+#pragma unroll
+      for (int u = 0; u < kSelRows; ++u) {
+        const int j = j0 + tid + u * kSelThreads;
+        sc[u] = (j >= g.mid_lo && j < g.mid_hi && j < j_end) ? score[j] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kSelRows; ++u) {
+        const int r = tid + u * kSelThreads;
+        lds_key[r + (r >> 4)] = score_key(sc[u]);
+      }
+      __syncthreads();
+    }
+    const int jt = j0 + tid * kSelRows;
+    bool sure[kSelRows], eq[kSelRows];
+    int n_sure = 0, n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < kSelRows; ++i) {
+      const int j = jt + i;
+      const bool in = j < j_end;
+      const bool middle = in && j >= g.mid_lo && j < g.mid_hi;
+      const uint32_t key = (middle && g.k > 0) ? lds_key[tid * (kSelRows + 1) + i] : 0u;
+      sure[i] = (in && !middle) || (middle && g.k > 0 && key > thr);
+      eq[i] = middle && g.k > 0 && key == thr;
+      n_sure += sure[i] ? 1 : 0;
+      n_eq += eq[i] ? 1 : 0;
+    }
+    int total;
+    const int excl = block_exclusive_scan(n_sure | (n_eq << 16), sm_scan, total);
+    const int place0 = sure_base + min(eq_base, need_eq);  // place of the tile's first survivor
+    int sure_before = sure_base + (excl & 0xffff);
+    int eq_before = eq_base + ((uint32_t)excl >> 16);
+    int first_out = n;
+#pragma unroll
+    for (int i = 0; i < kSelRows; ++i) {
+      const int j = jt + i;
+      const bool keep = sure[i] || (eq[i] && eq_before < need_eq);
+      if (keep) lds_out[sure_before + min(eq_before, need_eq) - place0] = j;
+      else if (j < j_end) first_out = min(first_out, j);
+      sure_before += sure[i] ? 1 : 0;
+      eq_before += eq[i] ? 1 : 0;
+    }
+    // rows leave in ascending order of the tiles, so only the first tile that evicts has to report
+    if (first_out < n && first_out < *(volatile int*)sh_first) atomicMin(sh_first, first_out);
+    sure_base += total & 0xffff;
+    eq_base += (uint32_t)total >> 16;
+    const int survivors = sure_base + min(eq_base, need_eq) - place0;
+    __syncthreads();
+    for (int i = tid; i < survivors; i += kSelThreads) kept[place0 + i] = lds_out[i];
+    __syncthreads();  // the LDS areas are free again
+  }
+}
+
+// Selection for the caches one workgroup can sweep alone (capacity up to kLongRows), long caches
+// first; longer caches are left to the tile kernels below.
 __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactParams p) {
   const int c = p.order[blockIdx.x];
+  if (p.cap[c] > kLongRows) return;
   const int tid = threadIdx.x;
-  const int n = p.len[c];
-  const int cpl = p.batch * p.Hkv;
-  const int b = p.budget[(c / cpl) * p.Hkv + c % p.Hkv];
+  const SelGoal g = sel_goal(p, c);
+  const int n = g.n;
   const int64_t off = p.off[c];
   int32_t* kept = p.kept + off;
   const float* score = p.score + off;
 
-  if (n <= b) {
+  if (n <= g.b) {
     if (p.write_identity)
       for (int j = tid; j < n; j += kSelThreads) kept[j] = j;
     if (tid == 0) p.info[c] = CompactInfo{n, n, n, 0};
     return;
   }
-  const int s = p.sink;
-  const int r = (p.policy == 1) ? (b - s) : p.recent;
-  const int k = b - s - r;  // middle rows that survive, >= 0 (checked at context creation)
-  const int mid_lo = s, mid_hi = n - r;
 
   __shared__ int hist[256];
   __shared__ int sm_scan[kSelWaves];
-  __shared__ uint32_t sh_prefix;
-  __shared__ int sh_need, sh_first;
+  __shared__ int sh_digit, sh_need, sh_first;
+  __shared__ uint32_t lds_key[kEmitKeyWords];
+  __shared__ int32_t lds_out[kEmitTile];
 
   uint32_t thr = 0;
   int need_eq = 0;
-  if (k > 0) {
+  if (g.k > 0) {
     // Radix select of the k-th largest key of the middle, 8 bits per pass, high digits first.
     uint32_t prefix = 0, mask = 0;
-    int need = k;
+    int need = g.k;
     for (int shift = 24; shift >= 0; shift -= 8) {
       for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
       __syncthreads();
-      // kSelUnroll independent loads per thread before the first use
-      for (int j0 = mid_lo + tid; j0 < mid_hi; j0 += kSelThreads * kSelUnroll) {
-        uint32_t key[kSelUnroll];
-#pragma unroll
-        for (int u = 0; u < kSelUnroll; ++u) {
-          const int j = j0 + u * kSelThreads;
-          key[u] = score_key(j < mid_hi ? score[j] : 0.f);
-        }
-#pragma unroll
-        for (int u = 0; u < kSelUnroll; ++u) {
-          const int j = j0 + u * kSelThreads;
-          const bool live = j < mid_hi && (key[u] & mask) == prefix;
-          const uint32_t digit = (key[u] >> shift) & 255;
-          if (live) atomicAdd(&hist[digit], 1);
-        }
-      }
+      count_digits<kSelUnroll>(score, g.mid_lo, g.mid_hi, prefix, mask, shift, hist);
       __syncthreads();
-      // The digit of the need-th largest key: thread t looks at digit 255 - t; `above` = keys with a
-      // larger digit.  Exactly one digit has above < need <= above + its own count.
-      {
-        const int mine = tid < 256 ? hist[255 - tid] : 0;
-        int all;
-        const int above = block_exclusive_scan(mine, sm_scan, all);
-        if (tid < 256 && above < need && above + mine >= need) {
-          sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-          sh_need = need - above;
-        }
-      }
-      __syncthreads();
-      prefix = sh_prefix;
+      find_digit(hist, need, sm_scan, &sh_digit, &sh_need);
+      prefix |= (uint32_t)sh_digit << shift;
       need = sh_need;
       mask |= 0xffu << shift;
       __syncthreads();
@@ -115,51 +232,158 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
     need_eq = need;  // rows whose key equals thr that still survive (oldest first)
   }
 
-  // Stable emit, kSelRows consecutive rows per thread and tile.  A row survives if it is a sink or
-  // recent row, if its key exceeds the threshold, or if it is among the first need_eq rows whose key
-  // equals it; its place in the list is the number of survivors before it, i.e. (rows of the first
-  // two kinds before it) + min(rows with an equal key before it, need_eq).  Both counts come from
-  // one workgroup scan of a packed pair (at most kSelRows * kSelThreads < 2^16 per tile).
   if (tid == 0) sh_first = n;
   __syncthreads();
-  int sure_base = 0, eq_base = 0;
-  for (int j0 = 0; j0 < n; j0 += kSelThreads * kSelRows) {
-    const int jt = j0 + tid * kSelRows;
-    uint32_t key[kSelRows];
-    bool sure[kSelRows], eq[kSelRows];
-    int n_sure = 0, n_eq = 0;
+  emit_rows(score, kept, g, thr, need_eq, 0, n, 0, 0, sm_scan, &sh_first, lds_key, lds_out);
+  __syncthreads();
+  if (tid == 0) p.info[c] = CompactInfo{g.b, sh_first, n, 0};
+}
+
+// ---- caches too long for one workgroup -------------------------------------------------------
+// A long cache is cut into tiles of kTileRows rows (over its capacity), one workgroup per tile and
+// pass.  Pass P (one kernel each, P = 0..3) leaves the 256 counters of every tile in the workspace;
+// a small kernel per pass sums them per cache and searches the digit: no atomics between
+// workgroups, no counters to clear, no waiting on another workgroup.  After the last pass the
+// counters also give the number of survivors in front of every tile, so that the emit kernel can
+// place its tile's rows without looking at the others.
+
+// After pass P a small kernel (one workgroup per long cache) sums the cache's tile counters, searches
+// the digit and stores the state of the selection; after the last pass it also turns the counters
+// into the number of survivors in front of every tile.
+template <int PASS>
+__global__ __launch_bounds__(256) void compact_digit_kernel(CompactParams p) {
+  const SelTile tl = p.tiles[p.long_first[blockIdx.x] - p.tile_base];  // tile 0 of the cache
+  const int c = tl.c;
+  const int tid = threadIdx.x;
+  const SelGoal g = sel_goal(p, c);
+  if (g.n <= g.b || g.k <= 0) return;
+  __shared__ int hist[256];
+  __shared__ int sm_scan[kSelWaves];
+  __shared__ int sh_digit, sh_need;
+  SelState st = PASS == 0 ? SelState{0u, g.k, {0, 0, 0, 0}} : p.sel_state[tl.first_tile];
+  int sum = 0;
+  for (int j = 0; j < tl.n_tiles; ++j) sum += p.tile_hist[((int64_t)(tl.first_tile + j) * 4 + PASS) * 256 + tid];
+  hist[tid] = sum;
+  __syncthreads();
+  // (find_digit's scan is written for kSelThreads threads; 256 fill the first four wavefront slots)
+  const int mine = hist[255 - tid];
+  int incl = mine;
+  const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-    for (int i = 0; i < kSelRows; ++i) {
-      const int j = jt + i;
-      const bool in = j < n;
-      const bool middle = in && j >= mid_lo && j < mid_hi;
-      key[i] = (middle && k > 0) ? score_key(score[j]) : 0u;
-      sure[i] = (in && !middle) || (middle && k > 0 && key[i] > thr);
-      eq[i] = middle && k > 0 && key[i] == thr;
-      n_sure += sure[i] ? 1 : 0;
-      n_eq += eq[i] ? 1 : 0;
-    }
-    int total;
-    const int excl = block_exclusive_scan(n_sure | (n_eq << 16), sm_scan, total);
-    int sure_before = sure_base + (excl & 0xffff);
-    int eq_before = eq_base + (excl >> 16);
-    int first_out = n;
-#pragma unroll
-    for (int i = 0; i < kSelRows; ++i) {
-      const int j = jt + i;
-      const bool keep = sure[i] || (eq[i] && eq_before < need_eq);
-      if (keep) kept[sure_before + min(eq_before, need_eq)] = j;
-      else if (j < n) first_out = min(first_out, j);
-      sure_before += sure[i] ? 1 : 0;
-      eq_before += eq[i] ? 1 : 0;
-    }
-    // rows leave in ascending order of the tiles, so only the first tile that evicts has to report
-    if (first_out < n && first_out < *(volatile int*)&sh_first) atomicMin(&sh_first, first_out);
-    sure_base += total & 0xffff;
-    eq_base += total >> 16;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) sm_scan[wave] = incl;
+  __syncthreads();
+  int above = incl - mine;
+  for (int w2 = 0; w2 < wave; ++w2) above += sm_scan[w2];
+  if (above < st.need && above + mine >= st.need) {
+    sh_digit = 255 - tid;
+    sh_need = st.need - above;
   }
   __syncthreads();
-  if (tid == 0) p.info[c] = CompactInfo{b, sh_first, n, 0};
+  st.prefix |= (uint32_t)sh_digit << (24 - 8 * PASS);
+  st.need = sh_need;
+  st.digit[PASS] = sh_digit;
+  if (tid == 0) p.sel_state[tl.first_tile] = st;
+  if (PASS == 3) {
+    // survivors in front of each tile: rows outside the middle, keys that some pass ranked above the
+    // threshold's digit, keys equal to the threshold (capped by need where they are used)
+    constexpr int kChunk = 512;  // tiles whose counts are staged in LDS at a time
+    __shared__ int tile_sure[kChunk], tile_eq[kChunk];
+    int run_sure = 0, run_eq = 0;  // thread 0: totals over the tiles so far
+    for (int j0 = 0; j0 < tl.n_tiles; j0 += kChunk) {
+      const int nj = min(kChunk, tl.n_tiles - j0);
+      for (int j = wave; j < nj; j += 4) {  // one wavefront per tile: its 64 lanes cover the 256 counters
+        const int32_t* th = p.tile_hist + (int64_t)(tl.first_tile + j0 + j) * 4 * 256;
+        int sure = 0, eq = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int d = lane + 64 * q;
+#pragma unroll
+          for (int ps = 0; ps < 4; ++ps) sure += d > st.digit[ps] ? th[ps * 256 + d] : 0;
+          eq += d == st.digit[3] ? th[3 * 256 + d] : 0;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+          sure += __shfl_xor(sure, o);
+          eq += __shfl_xor(eq, o);
+        }
+        if (lane == 0) { tile_sure[j] = sure; tile_eq[j] = eq; }
+      }
+      __syncthreads();
+      if (tid == 0) {
+        for (int j = 0; j < nj; ++j) {
+          p.tile_base_cnt[(int64_t)(tl.first_tile + j0 + j) * 2] = run_sure;
+          p.tile_base_cnt[(int64_t)(tl.first_tile + j0 + j) * 2 + 1] = run_eq;
+          run_sure += tile_sure[j];
+          run_eq += tile_eq[j];
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kSelThreads) void compact_tile_count_kernel(CompactParams p) {
+  const SelTile tl = p.tiles[blockIdx.x];
+  const int c = tl.c;
+  const int tid = threadIdx.x;
+  const SelGoal g = sel_goal(p, c);
+  if (PASS == 0 && tl.tile == 0 && tid == 0) {
+    // the selection's result record; the emit kernel lowers first_moved with atomicMin
+    p.info[c] = g.n <= g.b ? CompactInfo{g.n, g.n, g.n, 0} : CompactInfo{g.b, g.n, g.n, 0};
+  }
+  if (g.n <= g.b || g.k <= 0) return;  // nothing to rank (uniform over the cache's workgroups)
+  __shared__ int hist[256];
+  const uint32_t prefix = PASS == 0 ? 0u : p.sel_state[tl.first_tile].prefix;
+  for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
+  __syncthreads();
+  const int shift = 24 - 8 * PASS;
+  const uint32_t mask = PASS == 0 ? 0u : (0xffffffffu << (shift + 8));
+  const int j_begin = max(g.mid_lo, tl.tile * kTileRows), j_end = min(g.mid_hi, (tl.tile + 1) * kTileRows);
+  count_digits<kTileRows / kSelThreads>(p.score + p.off[c], j_begin, j_end, prefix, mask, shift, hist);
+  __syncthreads();
+  if (tid < 256) p.tile_hist[((int64_t)(tl.first_tile + tl.tile) * 4 + PASS) * 256 + tid] = hist[tid];
+}
+
+__global__ __launch_bounds__(kSelThreads) void compact_tile_emit_kernel(CompactParams p) {
+  const SelTile tl = p.tiles[blockIdx.x];
+  const int c = tl.c;
+  const int tid = threadIdx.x;
+  const SelGoal g = sel_goal(p, c);
+  const int n = g.n;
+  const int64_t off = p.off[c];
+  int32_t* kept = p.kept + off;
+  const int j_begin = tl.tile * kTileRows, j_end = min(n, (tl.tile + 1) * kTileRows);
+  if (n <= g.b) {
+    if (p.write_identity)
+      for (int j = j_begin + tid; j < j_end; j += kSelThreads) kept[j] = j;
+    return;
+  }
+  __shared__ int sm_scan[kSelWaves];
+  __shared__ int sh_first;
+  __shared__ uint32_t lds_key[kEmitKeyWords];
+  __shared__ int32_t lds_out[kEmitTile];
+  uint32_t thr = 0;
+  int need_eq = 0, sure_base = 0, eq_base = 0;
+  if (g.k > 0) {
+    const SelState st = p.sel_state[tl.first_tile];
+    thr = st.prefix;
+    need_eq = st.need;
+    sure_base = p.tile_base_cnt[(int64_t)(tl.first_tile + tl.tile) * 2];
+    eq_base = p.tile_base_cnt[(int64_t)(tl.first_tile + tl.tile) * 2 + 1];
+  }
+  const int before = min(j_begin, n);  // rows in front of this tile
+  sure_base += min(before, g.mid_lo) + max(0, before - g.mid_hi);
+  if (tid == 0) sh_first = n;
+  __syncthreads();
+  if (j_begin < j_end)
+    emit_rows(p.score + off, kept, g, thr, need_eq, j_begin, j_end, sure_base, eq_base, sm_scan, &sh_first, lds_key, lds_out);
+  __syncthreads();
+  if (tid == 0 && sh_first < n) atomicMin(&p.info[c].first_moved, sh_first);
 }
 
 constexpr int kMoveThreads = 512;
@@ -287,9 +511,21 @@ __global__ __launch_bounds__(kMoveThreads) void compact_move_kernel(CompactParam
 
 }  // namespace
 
-hipError_t launch_compact_select(const CompactParams& p, int n_caches, hipStream_t s) {
+hipError_t launch_compact_select(const CompactParams& p, int n_caches, int n_tiles, int n_long, hipStream_t s) {
   if (n_caches <= 0) return hipSuccess;
   compact_select_kernel<<<dim3(n_caches), dim3(kSelThreads), 0, s>>>(p);
+  if (n_tiles > 0) {
+    const dim3 grid(n_tiles), block(kSelThreads), per_cache(n_long);
+    compact_tile_count_kernel<0><<<grid, block, 0, s>>>(p);
+    compact_digit_kernel<0><<<per_cache, dim3(256), 0, s>>>(p);
+    compact_tile_count_kernel<1><<<grid, block, 0, s>>>(p);
+    compact_digit_kernel<1><<<per_cache, dim3(256), 0, s>>>(p);
+    compact_tile_count_kernel<2><<<grid, block, 0, s>>>(p);
+    compact_digit_kernel<2><<<per_cache, dim3(256), 0, s>>>(p);
+    compact_tile_count_kernel<3><<<grid, block, 0, s>>>(p);
+    compact_digit_kernel<3><<<per_cache, dim3(256), 0, s>>>(p);
+    compact_tile_emit_kernel<<<grid, block, 0, s>>>(p);
+  }
   return hipGetLastError();
 }
 

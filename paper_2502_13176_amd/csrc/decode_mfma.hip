@@ -388,9 +388,12 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
 
 // The recorded calls' weights without an attention call to ride on (baklava_flush_scores, and
 // baklava_compact before it ranks rows): a pass over the K rows alone.  Same work items, same
-// product and the same weights as in the attention kernel; K goes straight from HBM into the
-// operand layout (lane (row, j) reads elements 32c + 8j .. +8 of its row), one slab ahead.
+// product and the same weights as in the attention kernel, and the same route for K (whole rows
+// from HBM, staged in a wave-private LDS region, one slab ahead) and for the scores (read with the
+// slab, new values kept in LDS until the work item is done).
 __global__ __launch_bounds__(64 * kWaves) void score_flush_mfma(DecodeParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kWaves * kSlab * kKStride];
+  extern __shared__ __attribute__((aligned(16))) float lds_ring[];
   const Item it = p.items[blockIdx.x];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, jg = lane >> 4;
@@ -407,41 +410,62 @@ __global__ __launch_bounds__(64 * kWaves) void score_flush_mfma(DecodeParams p) 
   const int last = cnt - 1;
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.k) + it.row0 * (kD * 2);
   float* const sc_base = p.score + it.row0;
+  unsigned char* myk = lds_k + wave * (kSlab * kKStride);
+  float* ring = lds_ring + wave * p.ring_slots * kSlab;
   const float cs = p.scale_log2e;
-  u32x4_t a[2][4], an[2][4];
-  float sc_cur = 0.f, sc_next = 0.f;
-#define BAKLAVA_LOAD_SLAB(T0, dst, sc)                                                              \
-  _Pragma("unroll") for (int T = 0; T < 2; ++T) _Pragma("unroll") for (int c = 0; c < 4; ++c) {     \
-    const uint32_t off = (uint32_t)min((T0) + T * 16 + n16, last) * (kD * 2) + c * 64 + jg * 16;    \
-    dst[T][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off));             \
+  const uint32_t v_lane = n16 * 16;
+  u32x4_t kr[8];
+  float sc_cur = 0.f;
+  int ring_n = 0, ring_t0 = 0;
+  auto flush_ring = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int sidx = lane >> 5; sidx < ring_n; sidx += 2) {
+      const int r = ring_t0 + sidx * (kWaves * kSlab) + (lane & 31);
+      if (r < cnt) sc_base[r] = ring[sidx * kSlab + (lane & 31)];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    ring_n = 0;
+  };
+#define BAKLAVA_LOAD_SLAB(T0)                                                                       \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                   \
+    const uint32_t off = (uint32_t)min((T0) + jg + 4 * i, last) * (kD * 2) + v_lane;                \
+    kr[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off));                 \
   }                                                                                                 \
-  if (lane < kSlab) sc = sc_base[min((T0) + lane, last)];
+  if (lane < kSlab) sc_cur = sc_base[min((T0) + lane, last)];
   int t0 = wave * kSlab;
   if (t0 < cnt) {
-    BAKLAVA_LOAD_SLAB(t0, a, sc_cur)
+    BAKLAVA_LOAD_SLAB(t0)
   }
   for (; t0 < cnt; t0 += kWaves * kSlab) {
-    const int tn = t0 + kWaves * kSlab;
-    if (tn < cnt) {
-      BAKLAVA_LOAD_SLAB(tn, an, sc_next)
-    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(myk + (jg + 4 * i) * kKStride + n16 * 16) = kr[i];
+    const float sc_old = sc_cur;
+    BAKLAVA_LOAD_SLAB(t0 + kWaves * kSlab)  // past the end every row clamps to the last one: harmless re-reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     floatx4_t sp[2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
       sp[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a[T][c]), sp[T], 0, 0, 0);
+      for (int c = 0; c < 4; ++c) {
+        const u32x4_t a = *reinterpret_cast<const u32x4_t*>(myk + (T * 16 + n16) * kKStride + c * 64 + jg * 16);
+        sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
+      }
     }
     const float wr = record_weights(sp, rec, cs, it.start + t0, lane);
-    if (lane < kSlab && t0 + lane < cnt) sc_base[t0 + lane] = sc_cur + wr;
-#pragma unroll
-    for (int T = 0; T < 2; ++T)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) a[T][c] = an[T][c];
-    sc_cur = sc_next;
+    if (ring_n == 0) ring_t0 = t0;
+    if (lane < kSlab) ring[ring_n * kSlab + lane] = sc_old + wr;
+    if (++ring_n == p.ring_slots) flush_ring();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the staging area may be written again
   }
 #undef BAKLAVA_LOAD_SLAB
+  if (ring_n > 0) flush_ring();
 }
 
 }  // namespace
@@ -481,10 +505,15 @@ hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_cou
   return hipGetLastError();
 }
 
-hipError_t launch_score_flush_mfma(const DecodeParams& p, int n_items, hipStream_t s) {
+hipError_t launch_score_flush_mfma(const DecodeParams& p_in, int n_items, int max_count, hipStream_t s) {
   if (n_items <= 0) return hipSuccess;
-  if (p.G > 16) return hipErrorInvalidValue;
-  score_flush_mfma<<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
+  if (p_in.G > 16) return hipErrorInvalidValue;
+  DecodeParams p = p_in;
+  const int slot_bytes = kSlab * 4;
+  const int fit = (48 * 1024) / (kWaves * slot_bytes);  // beside the K staging area, within the default LDS limit
+  const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;
+  p.ring_slots = std::max(1, std::min(fit, need));
+  score_flush_mfma<<<dim3(n_items), dim3(64 * kWaves), (size_t)p.ring_slots * kWaves * slot_bytes, s>>>(p);
   return hipGetLastError();
 }
 

@@ -176,3 +176,40 @@ def test_long_caches_move_in_several_segments(slack):
         st2.score[c] = s
     run_compact_and_check(arena, w, st2)
     arena.close()
+
+
+@pytest.mark.parametrize("policy", [B.POLICY_SCORE, B.POLICY_STREAMING])
+@pytest.mark.parametrize("scores", ["uniform", "equal", "coarse", "signed_zero"])
+def test_caches_selected_tile_by_tile(scores, policy):
+    """Caches beyond 8192 rows of capacity are ranked by several workgroups (tiles of 8192 rows, one
+    kernel per radix pass): lengths at, just over and far over the budget, live lengths that end
+    inside the first, a middle and the last tile, ties that span tiles (the older row must win across
+    a tile boundary), short caches in the same launch, a launch over one layer only."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama32"], name="tiles", L=2, Hq=4, Hkv=4, batch=1, seed=26, sink=4,
+                     recent=16, slack=300)
+    rng = np.random.Generator(np.random.PCG64(w.seed + policy))
+    budgets = [8100, 8192, 8193, 20, 16300, 16384, 24581, 500]
+    extra = [300, 1, 150, 77, 0, 300, 299, 37]
+    arena = H.make_arena(w, budgets, policy=policy)
+    assert sum(1 for c in arena.cap_host if c > 8192) == 6
+    lens = [b + e for b, e in zip(budgets, extra)]
+    st = H.fill_from_host(arena, w, lens, rng, scores="uniform")
+    if scores != "uniform":
+        for c in range(arena.n_caches):
+            n = lens[c]
+            if scores == "equal":
+                s = np.full(n, 0.25, dtype=np.float32)
+            elif scores == "coarse":
+                s = (rng.integers(0, 7, n) / 8).astype(np.float32)
+            else:
+                s = np.where(rng.random(n) < 0.5, np.float32(0.0), np.float32(-0.0)).astype(np.float32)
+                s[rng.integers(0, n, 40)] = rng.random(40).astype(np.float32)
+                s[rng.integers(0, n, 40)] = -rng.random(40).astype(np.float32)
+            o = int(arena.off_host[c])
+            arena.score[o:o + n].copy_(torch.from_numpy(s).to(arena.device))
+            st.score[c] = s
+    after = run_compact_and_check(arena, w, st, policy=policy, layer_begin=1, layer_count=1)   # tiles of layer 1 only
+    after = run_compact_and_check(arena, w, after, policy=policy)                              # then both layers
+    run_compact_and_check(arena, w, after, policy=policy)                                      # nothing left to evict
+    arena.close()

@@ -56,9 +56,10 @@ int baklava_last_hip_error(void);
  * ------------------------------------------------------------------------------------------ */
 
 /*
- * Budgets proportional to importance (Methods, "Assigning Memory Budgets to KV-Caches": more
- * important heads get larger caches), clipped to [lo, hi] and rounded so that they sum to
- * global_budget exactly.  The paper prints no proportional rule; the rule used is integer-only:
+ * Budgets proportional to importance, clipped to [lo, hi] and rounded so that they sum to
+ * global_budget exactly.  This rule is not the paper's (its own allocation is Algorithm 2 below; its
+ * principle, Methods, "Assigning Memory Budgets to KV-Caches", is only that more important caches
+ * get more memory): it is the allocator the benchmark workloads ask for, made integer-only:
  *   w_i = max(1, floor(I_i / max(I) * 2^40)),  x_i(lam) = floor(lam * w_i / 2^40),
  *   lam = largest integer with sum_i clip(x_i) <= B,  b_i = clip(x_i(lam)),
  *   leftover tokens go one each to heads with lo <= x_i < hi in decreasing order of
@@ -77,14 +78,16 @@ int baklava_alloc_proportional(const double* importance, int32_t m, int64_t glob
  * the remainder one apiece to the most important first.  No cache below t, or all below t:
  * output equals input.  Increased sizes are not clipped.
  * importance HOST [m], size_in HOST [m], budget_out HOST [m] (may alias size_in).
- * Errors: EINVAL (null, m <= 0, r outside [0,1], negative size).
+ * Errors: EINVAL (null, m <= 0, r outside [0,1], negative size, an importance or t that is not
+ * finite: the algorithm orders importances and compares them with t).
  */
 int baklava_alloc_threshold(const double* importance, int32_t m, const int32_t* size_in,
                             double t, double r, int32_t* budget_out);
 
 /*
- * Arena layout replacing the per-head cache object of the paper's implementation (Methods,
- * last paragraph before Algorithm 1): cache c gets capacity budget[layer*Hkv+h] + slack rows at
+ * Arena layout replacing the per-head cache object of the paper's implementation (Methods: the
+ * method is implemented as a custom KV-cache object initialised once with the found budgets): cache
+ * c gets capacity budget[layer*Hkv+h] + slack rows at
  * token offset off[c] = sum of the capacities before it.
  * budget HOST [L*Hkv];  off_out HOST int64 [L*batch*Hkv];  cap_out HOST int32 [L*batch*Hkv];
  * total_tokens_out HOST scalar = rows each arena plane must hold.
@@ -123,6 +126,16 @@ int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int3
 
 /* ------------------------------------------------------------------------------------------
  * Device.
+ *
+ * Calls that only enqueue kernels on the caller's stream (safe inside a stream capture):
+ * baklava_reset, baklava_append, baklava_decode_attn, baklava_append_decode_attn (its token
+ * position and its capacity check are then those of the capture; baklava_append_decode_attn_replay
+ * is the variant made for replay), baklava_flush_scores, baklava_compact, and the one-time passes
+ * further down.  Set-up calls that synchronise or copy synchronously and therefore must stay
+ * outside a capture: baklava_create, baklava_set_option with the CHUNK_* and TARGET_* options
+ * (they rebuild and upload the work-item table after a device-wide synchronisation),
+ * baklava_set_lengths, baklava_sync_lengths, baklava_profile_read.  The stream arguments are
+ * hipStream_t handles passed as void* so that this header needs no HIP header.
  * ------------------------------------------------------------------------------------------ */
 
 typedef struct baklava_ctx baklava_ctx;
@@ -162,8 +175,11 @@ size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host
  * or call baklava_reset.  Writes the work-item table into the workspace with a synchronous copy.
  * Supported shapes: D in {64, 128}; Hq a multiple of Hkv with Hq/Hkv <= 16 (<= 8 for F32);
  * sink, recent >= 0.
- * Errors: EINVAL, EINFEASIBLE (some budget < sink + recent under POLICY_SCORE, or < sink under
- * POLICY_STREAMING), ECAPACITY (workspace_bytes too small, or len > cap), EHIP.
+ * The arena must be packed the way baklava_layout lays it out: off_host[c] = sum of the capacities
+ * of the caches before c (workspace planes that run parallel to the arena use the same offsets).
+ * Errors: EINVAL (also: offsets that are not the packed prefix sums), EINFEASIBLE (some budget <
+ * sink + recent under POLICY_SCORE, or < sink under POLICY_STREAMING), ECAPACITY (workspace_bytes
+ * too small, or len > cap), ENOMEM, EHIP.
  */
 int baklava_create(const baklava_desc* desc, const int64_t* off_host, const int32_t* cap_host,
                    const int32_t* len_host, const int32_t* budget_host, baklava_ctx** out);
@@ -289,27 +305,6 @@ int baklava_flush_scores(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_co
 int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
                     int32_t* kept_idx_out, void* stream);
 
-/*
- * Measurement aid for the dominant kernel (the split-K attention partial kernel, which reads all
- * of the K/V bytes of Eq. 7): with BAKLAVA_OPT_TIME_KERNEL set, baklava_decode_attn records a HIP
- * event on the caller's stream right before and right after that kernel.  This call waits for
- * the recorded events, returns the summed elapsed time and the number of launches since the last
- * read, and clears the record.  total_ms_out, launches_out HOST scalars.
- */
-int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out);
-
-/*
- * Measurement aid, independent of any context: streams `bytes` (a multiple of 16) through a
- * trivial kernel on `stream`.  mode 0 copies src to dst (both DEVICE, `bytes` long, 16-byte
- * aligned); modes 1 and 2 only read src, with ordinary and with non-temporal loads (dst DEVICE,
- * at least 1 KiB, is not meaningfully written); mode 3 is mode 2 on 64 workgroups only (what 64
- * compute units can pull on their own).
- * Used to calibrate the HBM byte counters against a transfer of known size and to measure the
- * bandwidth a plain streaming kernel reaches on the same device.
- * Errors: EINVAL (null, misaligned, bytes not a positive multiple of 16, bad mode), EHIP.
- */
-int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream);
-
 /* ------------------------------------------------------------------------------------------
  * One-time profiling (Algorithm 1), the step that produces the importance scores the budget
  * allocators above consume.
@@ -418,6 +413,34 @@ int baklava_kv_importance(const double* similarity_host, int32_t L, int32_t Hq, 
 
 /* Host mirror of the lengths; len_host_out HOST [n_caches].  No device access. */
 int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement aids.  Not part of the method: they exist so that the benchmark can time the dominant
+ * kernel on the stream it runs on and calibrate the HBM byte counters against a transfer of known
+ * size (together with BAKLAVA_OPT_TIME_KERNEL above).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Timing of the dominant kernel (the split-K attention partial kernel, which reads all
+ * of the K/V bytes of Eq. 7): with BAKLAVA_OPT_TIME_KERNEL set, baklava_decode_attn records a HIP
+ * event on the caller's stream right before and right after that kernel.  This call waits for
+ * the recorded events, returns the summed elapsed time and the number of launches since the last
+ * read, and clears the record.  total_ms_out, launches_out HOST scalars.
+ */
+int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out);
+
+/*
+ * Streaming probe, independent of any context: streams `bytes` (a multiple of 16) through a
+ * trivial kernel on `stream`.  mode 0 copies src to dst (both DEVICE, `bytes` long, 16-byte
+ * aligned); modes 1 and 2 only read src, with ordinary and with non-temporal loads (dst DEVICE,
+ * at least 1 KiB, is not meaningfully written); mode 3 is mode 2 on 64 workgroups only (what 64
+ * compute units can pull on their own).
+ * Used to calibrate the HBM byte counters against a transfer of known size and to measure the
+ * bandwidth a plain streaming kernel reaches on the same device.
+ * Errors: EINVAL (null, misaligned, bytes not a positive multiple of 16, bad mode), EHIP.
+ */
+int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream);
+
 
 #ifdef __cplusplus
 }

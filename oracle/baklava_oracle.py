@@ -124,6 +124,8 @@ def alloc_threshold(importance: Sequence[float], size_in: Sequence[int], t: floa
         raise ValueError("length mismatch")
     if not (0.0 <= r <= 1.0):
         raise ValueError("r must be in [0,1]")
+    if not math.isfinite(t) or not all(math.isfinite(v) for v in imp):
+        raise ValueError("importances and threshold must be finite: the algorithm orders and compares them")
     low = [i for i in range(m) if imp[i] < t]
     n = len(low)
     if n == m or n == 0:

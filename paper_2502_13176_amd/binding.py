@@ -14,8 +14,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# BAKLAVA_LIB lets a tuning run load a differently built copy of the same library.
-LIB_PATH = os.environ.get("BAKLAVA_LIB") or os.path.join(HERE, "libbaklava.so")
+LIB_PATH = os.path.join(HERE, "libbaklava.so")
 
 OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE, ENOMEM = range(7)
 BF16, F32 = 0, 1
@@ -320,6 +319,17 @@ def stream_probe(dst, src, nbytes: int, mode: int, stream=None) -> None:
                                       _stream_ptr(stream)), "baklava_stream_probe")
 
 
+def _hold_until_stream_passes(tensors, stream) -> None:
+    """Tensors allocated here on torch's current stream but used by kernels enqueued on another one:
+    the caching allocator must not hand their memory out again before that stream has passed the call
+    (the workspace is dropped as soon as the wrapper returns)."""
+    if stream is None:
+        return
+    for t in tensors:
+        if t is not None:
+            t.record_stream(stream)
+
+
 def kv_importance(similarity, L: int, Hq: int, Hkv: int) -> np.ndarray:
     """baklava_kv_importance: [L, Hq] head similarities -> [L, Hkv] KV-cache importances (host only)."""
     sim = np.ascontiguousarray(similarity, dtype=np.float64).reshape(-1)
@@ -356,6 +366,7 @@ def profile_similarity(q, k, v, want_cos: bool = True, want_lse: bool = False, s
                                             cos.data_ptr() if want_cos else None, sim.data_ptr(),
                                             lse.data_ptr() if want_lse else None, ws.data_ptr(),
                                             nbytes, _stream_ptr(stream)), "baklava_profile_similarity")
+    _hold_until_stream_passes((ws, sim, cos, lse), stream)
     return (sim, cos, lse) if want_lse else (sim, cos)
 
 
@@ -397,6 +408,7 @@ def layer_similarity(x_in, x_out, want_cos: bool = True, stream=None):
     _check(lib().baklava_layer_similarity(x_in.data_ptr(), x_out.data_ptr(), n_seq, T, hidden, BF16,
                                           cos.data_ptr() if want_cos else None, sim.data_ptr(), ws.data_ptr(), nbytes,
                                           _stream_ptr(stream)), "baklava_layer_similarity")
+    _hold_until_stream_passes((ws, sim, cos), stream)
     return sim, cos
 
 

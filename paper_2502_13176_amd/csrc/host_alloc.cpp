@@ -35,8 +35,9 @@ extern "C" const char* baklava_strerror(int status) {
   }
 }
 
-// Proportional budgets with an exact sum (Methods, "Assigning Memory Budgets to KV-Caches").
-// Fixed-point weights make every rounding an integer decision.
+// Proportional budgets with an exact sum: the allocator the benchmark workloads ask for (the paper
+// itself only states the principle that more important caches get more memory, and gives
+// Algorithm 2).  Fixed-point weights make every rounding an integer decision.
 extern "C" int baklava_alloc_proportional(const double* importance, int32_t m, int64_t global_budget,
                                           int32_t lo, int32_t hi, int32_t* budget_out) {
   if (!importance || !budget_out || m <= 0 || lo < 0 || hi < lo || global_budget < 0) return BAKLAVA_EINVAL;
@@ -100,11 +101,12 @@ extern "C" int baklava_alloc_proportional(const double* importance, int32_t m, i
 extern "C" int baklava_alloc_threshold(const double* importance, int32_t m, const int32_t* size_in,
                                        double t, double r, int32_t* budget_out) {
   if (!importance || !size_in || !budget_out || m <= 0) return BAKLAVA_EINVAL;
-  if (!(r >= 0.0 && r <= 1.0)) return BAKLAVA_EINVAL;
+  if (!(r >= 0.0 && r <= 1.0) || !std::isfinite(t)) return BAKLAVA_EINVAL;
   std::vector<int64_t> size(m);
   std::vector<int32_t> low, high;
   for (int32_t i = 0; i < m; ++i) {
-    if (size_in[i] < 0) return BAKLAVA_EINVAL;
+    // the algorithm orders importances and compares them with t: a NaN has no place in either
+    if (size_in[i] < 0 || !std::isfinite(importance[i])) return BAKLAVA_EINVAL;
     size[i] = size_in[i];
     (importance[i] < t ? low : high).push_back(i);
   }

@@ -39,6 +39,12 @@ int main() {
     for (int i = 0; i < m; ++i) { s0 += size[i]; s1 += out[i]; }
     CHECK(s0 == s1);
     CHECK(baklava_alloc_threshold(u.data(), m, size.data(), 0.5, 0.3, size.data()) == BAKLAVA_OK);  // aliasing allowed
+    // a NaN importance would make the ordering of the receivers undefined: refused, like a NaN threshold
+    const double keep = u[m / 2];
+    u[m / 2] = std::nan("");
+    CHECK(baklava_alloc_threshold(u.data(), m, size.data(), 0.5, 0.3, out.data()) == BAKLAVA_EINVAL);
+    u[m / 2] = keep;
+    CHECK(baklava_alloc_threshold(u.data(), m, size.data(), std::nan(""), 0.3, out.data()) == BAKLAVA_EINVAL);
   }
   // extreme weights: tiny importances next to a huge one, and a single head
   {

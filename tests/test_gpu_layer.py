@@ -78,3 +78,28 @@ def test_error_paths():
     assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 64, B.BF16, None, sim.data_ptr(), ws.data_ptr(), 0, None) == B.ECAPACITY
     assert L.baklava_layer_similarity(a.data_ptr(), a.data_ptr(), 1, 4, 64, B.BF16, None, sim.data_ptr(), ws.data_ptr(), 256, None) == B.OK
     torch.cuda.synchronize()
+
+
+def test_one_time_passes_on_a_side_stream():
+    """The wrappers allocate the kernels' workspace themselves; when the kernels run on a stream other
+    than the current one, that memory must stay theirs until the stream has passed the call, whatever
+    the current stream allocates meanwhile."""
+    H = _h()
+    dev = torch.device("cuda:0")
+    rng = np.random.Generator(np.random.PCG64(9970))
+    a = H.to_device_storage(synth.payload(rng, (4, 2048, 2048), "bf16"), "bf16", dev)
+    b = H.to_device_storage(synth.payload(rng, (4, 2048, 2048), "bf16"), "bf16", dev)
+    q = H.to_device_storage(synth.payload(rng, (1, 8, 2048, 128), "bf16"), "bf16", dev)
+    kv = H.to_device_storage(synth.payload(rng, (1, 2, 2048, 128), "bf16"), "bf16", dev)
+    want_layer, _ = B.layer_similarity(a, b)
+    want_head, _ = B.profile_similarity(q, kv, kv)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    got_layer, _ = B.layer_similarity(a, b, stream=side)
+    got_head, _ = B.profile_similarity(q, kv, kv, stream=side)
+    churn = [torch.full((4096,), 0xFF, dtype=torch.uint8, device=dev) for _ in range(64)]   # would reuse a freed workspace
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(got_layer, want_layer) and torch.equal(got_head, want_head)
+    del churn

@@ -79,6 +79,38 @@ def test_threshold_error_codes():
     with pytest.raises(B.BaklavaError) as e:
         B.alloc_threshold([0.1, 0.9], [10, 10], 0.5, 1.5)
     assert e.value.status == B.EINVAL
+    # Algorithm 2 orders importances and compares them with t: a NaN or an infinity has no place there,
+    # on either side
+    for imp, t in (([0.1, float("nan"), 0.9], 0.5), ([0.1, float("inf"), 0.9], 0.5), ([0.1, 0.9], float("nan"))):
+        with pytest.raises(B.BaklavaError) as e:
+            B.alloc_threshold(imp, [10] * len(imp), t, 0.5)
+        assert e.value.status == B.EINVAL
+        with pytest.raises(ValueError):
+            O.alloc_threshold(imp, [10] * len(imp), t, 0.5)
+    with pytest.raises(B.BaklavaError) as e:
+        B.alloc_two_level([1.0, 2.0], [[0.2, float("nan")], [0.5, 0.6]], 400, 10, 400, 0.5, 0.5)
+    assert e.value.status == B.EINVAL
+
+
+def test_create_refuses_an_arena_that_is_not_packed():
+    """The offsets must be the packed prefix sums of the capacities (what baklava_layout writes): the
+    check comes before anything touches a device, so it runs without one."""
+    w = synth.WORKLOADS["tiny"]
+    b = np.asarray([64, 192], dtype=np.int32)
+    off, cap, total = B.layout(b, w.L, w.Hkv, w.batch, w.slack)
+    d = B.Desc()
+    d.L, d.Hq, d.Hkv, d.D, d.batch, d.dtype = w.L, w.Hq, w.Hkv, w.D, w.batch, B.F32
+    d.sink, d.recent = w.sink, w.recent
+    fake = 0x1000                                         # never dereferenced: the call fails on the offsets
+    d.k = d.v = d.score = d.pos = d.off = d.cap = d.len = d.budget = d.workspace = fake
+    d.workspace_bytes = 1 << 30
+    i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    for bad in (off + np.array([0, 16]), off[::-1].copy(), off + 8):
+        bad = np.ascontiguousarray(bad, dtype=np.int64)
+        ctx = C.c_void_p()
+        st = B.lib().baklava_create(C.byref(d), bad.ctypes.data_as(i64p), cap.ctypes.data_as(i32p), None,
+                                    b.ctypes.data_as(i32p), C.byref(ctx))
+        assert st == B.EINVAL and not ctx.value
 
 
 @pytest.mark.parametrize("name", ["tiny", "llama1", "qwen"])

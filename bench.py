@@ -251,7 +251,8 @@ def prefill_row(torch, B, synth, device, with_cpu_baseline, T=32768, reps=5):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     flops = Hq * D * T * (T + 1)
-    e0.record()
+    run()                      # the eviction follows the scores on the stream, as in a prefill: the device is
+    e0.record()                # still busy while the host enqueues it, so the events time the device's work
     arena.compact(0, 1)
     e1.record()
     torch.cuda.synchronize()

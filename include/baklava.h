@@ -132,8 +132,8 @@ int baklava_plan_schedule(const int64_t* off_host, const int32_t* cap_host, int3
  * position and its capacity check are then those of the capture; baklava_append_decode_attn_replay
  * is the variant made for replay), baklava_flush_scores, baklava_compact, and the one-time passes
  * further down.  Set-up calls that synchronise or copy synchronously and therefore must stay
- * outside a capture: baklava_create, baklava_set_option with the CHUNK_* and TARGET_* options
- * (they rebuild and upload the work-item table after a device-wide synchronisation),
+ * outside a capture: baklava_create, baklava_set_option with the CHUNK_*, TARGET_* and
+ * TILED_SELECT_ROWS options (they rebuild and upload a table after a device-wide synchronisation),
  * baklava_set_lengths, baklava_sync_lengths, baklava_profile_read.  The stream arguments are
  * hipStream_t handles passed as void* so that this header needs no HIP header.
  * ------------------------------------------------------------------------------------------ */
@@ -200,9 +200,13 @@ enum {
                                    otherwise five times that number, with a shortest run of 256 rows */
   BAKLAVA_OPT_TARGET_ITEMS_WHOLE = 6, /* the same for launches over all layers at once.  Default: five
                                    times the device's number of compute units                      */
-  BAKLAVA_OPT_TRACK_SCORES = 7  /* 0: attention calls stop adding to the scores (calls already on
+  BAKLAVA_OPT_TRACK_SCORES = 7, /* 0: attention calls stop adding to the scores (calls already on
                                    record stay there until the next flush); 1: they resume.  Only a
                                    context created with track_scores can be switched to 1          */
+  BAKLAVA_OPT_TILED_SELECT_ROWS = 8 /* eviction: caches whose capacity exceeds this many rows are ranked
+                                   by several workgroups (tiles of 8192 rows) instead of one.
+                                   >= 8192; default 36864, or 8192 for a context of fewer than 512
+                                   caches.  Synchronises like the CHUNK options                   */
 };
 int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t value);
 

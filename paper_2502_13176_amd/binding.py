@@ -20,7 +20,7 @@ OK, EINVAL, EINFEASIBLE, ECAPACITY, EHIP, ESTATE, ENOMEM = range(7)
 BF16, F32 = 0, 1
 POLICY_SCORE, POLICY_STREAMING = 0, 1
 OPT_CHUNK_TOKENS, OPT_KERNEL, OPT_TIME_KERNEL, OPT_CHUNK_TOKENS_WHOLE, OPT_TARGET_ITEMS, OPT_TARGET_ITEMS_WHOLE = 1, 2, 3, 4, 5, 6
-OPT_TRACK_SCORES = 7
+OPT_TRACK_SCORES, OPT_TILED_SELECT_ROWS = 7, 8
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = [

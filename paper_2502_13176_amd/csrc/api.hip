@@ -27,6 +27,14 @@ constexpr int kDefaultChunk = 512;        // launches over part of the model: sh
 constexpr int kDefaultChunkWhole = 256;   // launches over the whole model: shortest run; longer ones come from the item target
 constexpr int kWholeItemsPerCu = 5;       // whole-model launches aim at this many work items per compute unit
 constexpr int kMaxChunk = 1 << 22; // row offsets inside a work item stay below 2^32 bytes
+// Eviction: caches beyond this capacity are ranked by several workgroups.  One workgroup sweeps a cache
+// five times out of the L2 and is bound by latency (about 80 us for 32768 rows); with thousands of
+// caches in flight that latency is hidden and one workgroup per cache is the cheaper way up to about
+// that size (measured on the 2048 llama32 caches: 175 us one workgroup each, 240 us with a threshold
+// of 8192 rows), with a few caches (a prompt of one sequence: 8 caches of 32768 rows) it is not
+// (82 us against 47 us tile by tile).
+constexpr int kDefaultLongRows = 36864;
+constexpr int kFewCaches = 512;  // below this many caches every cache beyond one tile is ranked tile by tile
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -40,7 +48,7 @@ struct WorkspacePlan {
   // index 0: schedule for launches over a layer sub-range, 1: for launches over the whole model
   size_t items[2], multi[2];
   size_t part_o, part_ml, final_ml, lag_q, lag_ml, lag_n, lag_cnt, status, kept, info, order_all, order_layer;
-  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, tiles, tile_hist, sel_state, tile_base_cnt, long_first, total;
+  size_t segs, seg_split, halo_k, halo_v, halo_score, halo_pos, tiles, tile_hist, sel_state, total;
   int64_t n_segs, halo_rows, n_tiles, n_long;
   int64_t max_items;
 };
@@ -115,15 +123,13 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   w.n_tiles = 0;
   w.n_long = 0;
   for (int64_t c = 0; c < n_caches; ++c)
-    if (cap[c] > kLongRows) {
+    if (cap[c] > kMinLongRows) {  // room for every threshold BAKLAVA_OPT_TILED_SELECT_ROWS may set
       w.n_tiles += ((int64_t)cap[c] + kTileRows - 1) / kTileRows;
       w.n_long += 1;
     }
   w.tiles = o;        o = align256(o + (size_t)w.n_tiles * sizeof(SelTile));
   w.tile_hist = o;    o = align256(o + (size_t)w.n_tiles * 4 * 256 * 4);
-  w.sel_state = o;    o = align256(o + (size_t)w.n_tiles * sizeof(SelState));
-  w.tile_base_cnt = o; o = align256(o + (size_t)w.n_tiles * 2 * 4);
-  w.long_first = o;   o = align256(o + (size_t)w.n_long * 4);
+  w.sel_state = o;    o = align256(o + (size_t)w.n_long * 4 * sizeof(SelState));
   w.total = o;
   return w;
 }
@@ -141,12 +147,12 @@ struct baklava_ctx {
   std::vector<int32_t> order_all, order_layer;  // caches, longest first (whole model / inside each layer)
   std::vector<int32_t> seg_begin;               // cache -> first segment of the eviction move
   std::vector<int32_t> tile_begin;              // cache -> first tile of the tiled selection (long caches only have any)
-  std::vector<int32_t> long_begin;              // cache -> number of long caches before it
   int32_t kernel_pref;
   bool layer_one_wave;   // default schedule of layer-range launches: one workgroup per compute unit
   int32_t target_items;  // > 0: layer-range launches lengthen their runs until a layer has at most this many items
   int32_t target_items_whole;  // > 0: the same for launches over the whole model
   int32_t n_cus;               // compute units of the device
+  int32_t select_long_rows;    // caches with more capacity than this are ranked tile by tile at eviction
   int32_t lag_gp_log2;         // score tracking: log2 of G rounded up to 4, 8 or 16 (rows a call takes in a record)
   struct Schedule {
     int32_t chunk = 0;
@@ -204,6 +210,31 @@ int build_schedule(baklava_ctx* ctx, int which, int chunk) {
   ctx->sched[which].multi_begin.swap(multi_begin);
   ctx->sched[which].chunk = chunk;
   ctx->sched[which].max_count.swap(max_count);
+  return BAKLAVA_OK;
+}
+
+// Tile table of the eviction's selection for long caches (depends on capacities and the threshold
+// only), in cache order, so that the tiles of a layer range are a contiguous slice.
+int build_tiles(baklava_ctx* ctx) {
+  std::vector<SelTile> tiles;
+  const int64_t n_caches = ctx->n_caches;
+  std::vector<int32_t> tile_begin(n_caches + 1, 0);
+  int32_t n_long = 0;
+  for (int64_t c = 0; c < n_caches; ++c) {
+    tile_begin[c] = (int32_t)tiles.size();
+    if (ctx->cap[c] <= ctx->select_long_rows) continue;
+    const int32_t nt = (int32_t)(((int64_t)ctx->cap[c] + kTileRows - 1) / kTileRows);
+    const int32_t first = (int32_t)tiles.size();
+    for (int32_t t = 0; t < nt; ++t) tiles.push_back(SelTile{(int32_t)c, t, first, nt, n_long, 0});
+    n_long += 1;
+  }
+  tile_begin[n_caches] = (int32_t)tiles.size();
+  if ((int64_t)tiles.size() > ctx->plan.n_tiles || n_long > ctx->plan.n_long) return BAKLAVA_ECAPACITY;
+  if (!hip_ok(hipDeviceSynchronize())) return BAKLAVA_EHIP;  // no launch may still read the old table
+  if (!tiles.empty() &&
+      !hip_ok(hipMemcpy(ctx->ws + ctx->plan.tiles, tiles.data(), tiles.size() * sizeof(SelTile), hipMemcpyHostToDevice)))
+    return BAKLAVA_EHIP;
+  ctx->tile_begin.swap(tile_begin);
   return BAKLAVA_OK;
 }
 
@@ -475,32 +506,10 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
       return BAKLAVA_EHIP;
     }
   }
-  // Tile table of the selection for long caches (depends on capacities only), in cache order, so that
-  // the tiles of a layer range are a contiguous slice.
+  ctx->select_long_rows = n_caches < kFewCaches ? kMinLongRows : kDefaultLongRows;
   {
-    std::vector<SelTile> tiles;
-    std::vector<int32_t> long_first;
-    tiles.reserve((size_t)ctx->plan.n_tiles);
-    ctx->tile_begin.assign(n_caches + 1, 0);
-    ctx->long_begin.assign(n_caches + 1, 0);
-    for (int64_t c = 0; c < n_caches; ++c) {
-      ctx->tile_begin[c] = (int32_t)tiles.size();
-      ctx->long_begin[c] = (int32_t)long_first.size();
-      if (ctx->cap[c] <= kLongRows) continue;
-      const int32_t nt = (int32_t)(((int64_t)ctx->cap[c] + kTileRows - 1) / kTileRows);
-      const int32_t first = (int32_t)tiles.size();
-      long_first.push_back(first);
-      for (int32_t t = 0; t < nt; ++t) tiles.push_back(SelTile{(int32_t)c, t, first, nt});
-    }
-    ctx->tile_begin[n_caches] = (int32_t)tiles.size();
-    ctx->long_begin[n_caches] = (int32_t)long_first.size();
-    if ((int64_t)tiles.size() != ctx->plan.n_tiles || (int64_t)long_first.size() != ctx->plan.n_long ||
-        (!tiles.empty() &&
-         (!hip_ok(hipMemcpy(ctx->ws + ctx->plan.tiles, tiles.data(), tiles.size() * sizeof(SelTile), hipMemcpyHostToDevice)) ||
-          !hip_ok(hipMemcpy(ctx->ws + ctx->plan.long_first, long_first.data(), long_first.size() * 4, hipMemcpyHostToDevice))))) {
-      delete ctx;
-      return BAKLAVA_EHIP;
-    }
+    const int st = build_tiles(ctx);
+    if (st != BAKLAVA_OK) { delete ctx; return st; }
   }
   if (!hip_ok(prepare_decode_mfma())) { delete ctx; return BAKLAVA_EHIP; }
   int st = build_schedule(ctx, 0, ctx->layer_one_wave ? kDefaultChunk : kDefaultChunkWhole);
@@ -542,6 +551,15 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       if (value == 1 && ctx->G > 8) return BAKLAVA_EINVAL;
       ctx->kernel_pref = (int32_t)value;
       return BAKLAVA_OK;
+    case BAKLAVA_OPT_TILED_SELECT_ROWS: {
+      if (value < kMinLongRows || value > INT32_MAX) return BAKLAVA_EINVAL;
+      if ((int32_t)value == ctx->select_long_rows) return BAKLAVA_OK;
+      const int32_t old = ctx->select_long_rows;
+      ctx->select_long_rows = (int32_t)value;
+      const int st = build_tiles(ctx);
+      if (st != BAKLAVA_OK) ctx->select_long_rows = old;
+      return st;
+    }
     case BAKLAVA_OPT_TRACK_SCORES:
       if (value != 0 && value != 1) return BAKLAVA_EINVAL;
       if (value == 1 && !ctx->d.track_scores) return BAKLAVA_EINVAL;  // the workspace holds no records
@@ -700,11 +718,8 @@ extern "C" int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t la
   p.tiles = reinterpret_cast<const SelTile*>(ctx->ws + ctx->plan.tiles) + t0;
   p.tile_hist = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.tile_hist);
   p.sel_state = reinterpret_cast<SelState*>(ctx->ws + ctx->plan.sel_state);
-  p.tile_base_cnt = reinterpret_cast<int32_t*>(ctx->ws + ctx->plan.tile_base_cnt);
-  const int32_t l0 = ctx->long_begin[c0], l1 = ctx->long_begin[c1];
-  p.long_first = reinterpret_cast<const int32_t*>(ctx->ws + ctx->plan.long_first) + l0;
-  p.tile_base = t0;
-  if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), t1 - t0, l1 - l0, s))) return BAKLAVA_EHIP;
+  p.long_rows = ctx->select_long_rows;
+  if (!hip_ok(launch_compact_select(p, (int)(c1 - c0), t1 - t0, s))) return BAKLAVA_EHIP;
   if (!hip_ok(launch_compact_move(p, s1 - s0, s))) return BAKLAVA_EHIP;
   for (int64_t c = c0; c < c1; ++c) {
     const int32_t b = ctx->budget[(c / ctx->cpl) * ctx->d.Hkv + c % ctx->d.Hkv];

@@ -21,8 +21,8 @@ __device__ __forceinline__ void store_nt16(void* ptr, uint4 v) {
 #endif
 
 constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move
-constexpr int kLongRows = 8192;     // caches with more capacity than this are selected tile by tile
-constexpr int kTileRows = 8192;     // rows per tile of such a cache (one workgroup per tile and pass)
+constexpr int kTileRows = 8192;     // rows per tile of a cache that is ranked tile by tile (one workgroup per tile and pass)
+constexpr int kMinLongRows = kTileRows;  // smallest capacity from which a cache may be ranked that way
 
 // One split-K work item (same layout as baklava_work_item of the public header): rows
 // [start, start + count) of cache c; its partial result goes to partial slot `slot`.  Rows at or
@@ -47,9 +47,11 @@ struct SelTile {
   int32_t c, tile;
   int32_t first_tile;  // index of the cache's tile 0 in the tile table
   int32_t n_tiles;     // tiles of the cache
+  int32_t long_idx;    // index of the cache among the caches that are ranked this way
+  int32_t pad;
 };
 
-// State of the radix select of a long cache after a pass (stored at the cache's first tile).
+// State of the radix select of a long cache after a pass.
 struct SelState {
   uint32_t prefix;   // digits found so far, in place
   int32_t need;      // rank of the wanted key among the keys that match the prefix
@@ -168,10 +170,8 @@ struct CompactParams {
   const int32_t* cap;
   const SelTile* tiles;    // tiles of the long caches of the launched range
   int32_t* tile_hist;      // [all tiles][4 passes][256] digit counters, indexed by first_tile + tile
-  SelState* sel_state;     // [all tiles], entry first_tile of a cache is used
-  int32_t* tile_base_cnt;  // [all tiles][2] survivors / threshold-equal keys in front of a tile
-  const int32_t* long_first;  // long caches of the launched range -> index of their first tile
-  int32_t tile_base;       // index of tiles[0] in the whole tile table
+  SelState* sel_state;     // [long caches][4] state after pass 0..3
+  int32_t long_rows;       // caches with more capacity than this are ranked tile by tile
 };
 
 // Records a failed HIP call for baklava_last_hip_error() (per host thread).
@@ -198,7 +198,7 @@ hipError_t launch_combine(const DecodeParams& p, int D, int n_multi, hipStream_t
 hipError_t launch_score_pass(const ScoreParams& p, int dtype, int D, int n_items, int max_count, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, int n_caches, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* dst, int32_t value, int64_t n, hipStream_t s);
-hipError_t launch_compact_select(const CompactParams& p, int n_caches, int n_tiles, int n_long, hipStream_t s);
+hipError_t launch_compact_select(const CompactParams& p, int n_caches, int n_tiles, hipStream_t s);
 hipError_t launch_compact_move(const CompactParams& p, int n_segs, hipStream_t s);
 hipError_t launch_stream_probe(void* dst, const void* src, int64_t bytes, int mode, hipStream_t s);
 

@@ -112,7 +112,8 @@ __device__ __forceinline__ void find_digit(const int* hist, int need, int* sm_sc
 }
 
 // LDS an emit needs: the keys of a tile, padded by one word per 16 so that a thread's 16 consecutive
-// keys and its neighbours' fall into different banks, and the tile's part of the kept list.
+// keys and its neighbours' fall into different banks; once every thread has read its keys (the
+// workgroup scan in between has barriers) the same words collect the tile's part of the kept list.
 constexpr int kEmitKeyWords = kEmitTile + kEmitTile / 16;
 
 // Stable emit of the rows [j_begin, j_end) of a cache.  A row survives if it is a sink or recent
@@ -128,21 +129,24 @@ constexpr int kEmitKeyWords = kEmitTile + kEmitTile / 16;
 // to *sh_first (shared, initialised by the caller to the cache's length).
 __device__ __forceinline__ void emit_rows(const float* score, int32_t* kept, const SelGoal& g, uint32_t thr,
                                           int need_eq, int j_begin, int j_end, int sure_base, int eq_base,
-                                          int* sm_scan, int* sh_first, uint32_t* lds_key, int32_t* lds_out) {
+                                          int* sm_scan, int* sh_first, uint32_t* lds_key) {
   const int tid = threadIdx.x;
   const int n = g.n;
+  int32_t* lds_out = reinterpret_cast<int32_t*>(lds_key);
   for (int j0 = j_begin; j0 < j_end; j0 += kEmitTile) {
+    const int live = j_end - j0;  // rows of this tile (a short cache fills only the front of it)
     if (g.k > 0) {
       float sc[kSelRows];
 #pragma unroll
       for (int u = 0; u < kSelRows; ++u) {
         const int j = j0 + tid + u * kSelThreads;
-        sc[u] = (j >= g.mid_lo && j < g.mid_hi && j < j_end) ? score[j] : 0.f;
+        sc[u] = 0.f;
+        if (u * kSelThreads < live) sc[u] = (j >= g.mid_lo && j < g.mid_hi && j < j_end) ? score[j] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < kSelRows; ++u) {
         const int r = tid + u * kSelThreads;
-        lds_key[r + (r >> 4)] = score_key(sc[u]);
+        if (u * kSelThreads < live) lds_key[r + (r >> 4)] = score_key(sc[u]);
       }
       __syncthreads();
     }
@@ -186,11 +190,11 @@ __device__ __forceinline__ void emit_rows(const float* score, int32_t* kept, con
   }
 }
 
-// Selection for the caches one workgroup can sweep alone (capacity up to kLongRows), long caches
+// Selection for the caches one workgroup sweeps alone (capacity up to p.long_rows), long caches
 // first; longer caches are left to the tile kernels below.
 __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactParams p) {
   const int c = p.order[blockIdx.x];
-  if (p.cap[c] > kLongRows) return;
+  if (p.cap[c] > p.long_rows) return;
   const int tid = threadIdx.x;
   const SelGoal g = sel_goal(p, c);
   const int n = g.n;
@@ -209,7 +213,6 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
   __shared__ int sm_scan[kSelWaves];
   __shared__ int sh_digit, sh_need, sh_first;
   __shared__ uint32_t lds_key[kEmitKeyWords];
-  __shared__ int32_t lds_out[kEmitTile];
 
   uint32_t thr = 0;
   int need_eq = 0;
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
 
   if (tid == 0) sh_first = n;
   __syncthreads();
-  emit_rows(score, kept, g, thr, need_eq, 0, n, 0, 0, sm_scan, &sh_first, lds_key, lds_out);
+  emit_rows(score, kept, g, thr, need_eq, 0, n, 0, 0, sm_scan, &sh_first, lds_key);
   __syncthreads();
   if (tid == 0) p.info[c] = CompactInfo{g.b, sh_first, n, 0};
 }
@@ -242,88 +245,36 @@ __global__ __launch_bounds__(kSelThreads) void compact_select_kernel(CompactPara
 // ---- caches too long for one workgroup -------------------------------------------------------
 // A long cache is cut into tiles of kTileRows rows (over its capacity), one workgroup per tile and
 // pass.  Pass P (one kernel each, P = 0..3) leaves the 256 counters of every tile in the workspace;
-// a small kernel per pass sums them per cache and searches the digit: no atomics between
-// workgroups, no counters to clear, no waiting on another workgroup.  After the last pass the
-// counters also give the number of survivors in front of every tile, so that the emit kernel can
-// place its tile's rows without looking at the others.
+// the counters of a cache are the sums over its tiles, which every workgroup of the next kernel forms
+// for itself (a few thousand additions) before it searches the digit: no atomics between workgroups,
+// no counters to clear, no waiting on another workgroup, and one kernel per pass.  The last kernel
+// knows the threshold, derives from the stored counters how many survivors the tiles before its own
+// hold, and emits its tile.
 
-// After pass P a small kernel (one workgroup per long cache) sums the cache's tile counters, searches
-// the digit and stores the state of the selection; after the last pass it also turns the counters
-// into the number of survivors in front of every tile.
-template <int PASS>
-__global__ __launch_bounds__(256) void compact_digit_kernel(CompactParams p) {
-  const SelTile tl = p.tiles[p.long_first[blockIdx.x] - p.tile_base];  // tile 0 of the cache
-  const int c = tl.c;
+// State of a long cache's selection after pass P - 1, formed by every workgroup of the kernel that
+// follows that pass: the state after pass P - 2 (stored by that kernel's predecessor) advanced by
+// the digit search on the summed tile counters of pass P - 1.  Tile 0's workgroup stores it for the
+// next kernel.  Ends with a barrier; `hist` is free again.
+template <int P>
+__device__ __forceinline__ SelState state_before_pass(const CompactParams& p, const SelTile& tl, int k, int* hist,
+                                                      int* sm_scan, int* sh_digit, int* sh_need) {
+  SelState st = SelState{0u, k, {0, 0, 0, 0}};
+  if (P == 0) return st;
+  if (P >= 2) st = p.sel_state[(int64_t)tl.long_idx * 4 + (P - 2)];
   const int tid = threadIdx.x;
-  const SelGoal g = sel_goal(p, c);
-  if (g.n <= g.b || g.k <= 0) return;
-  __shared__ int hist[256];
-  __shared__ int sm_scan[kSelWaves];
-  __shared__ int sh_digit, sh_need;
-  SelState st = PASS == 0 ? SelState{0u, g.k, {0, 0, 0, 0}} : p.sel_state[tl.first_tile];
-  int sum = 0;
-  for (int j = 0; j < tl.n_tiles; ++j) sum += p.tile_hist[((int64_t)(tl.first_tile + j) * 4 + PASS) * 256 + tid];
-  hist[tid] = sum;
-  __syncthreads();
-  // (find_digit's scan is written for kSelThreads threads; 256 fill the first four wavefront slots)
-  const int mine = hist[255 - tid];
-  int incl = mine;
-  const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o);
-    if (lane >= o) incl += t;
-  }
-  if (lane == 63) sm_scan[wave] = incl;
-  __syncthreads();
-  int above = incl - mine;
-  for (int w2 = 0; w2 < wave; ++w2) above += sm_scan[w2];
-  if (above < st.need && above + mine >= st.need) {
-    sh_digit = 255 - tid;
-    sh_need = st.need - above;
+  if (tid < 256) {
+    int sum = 0;
+    for (int j = 0; j < tl.n_tiles; ++j) sum += p.tile_hist[((int64_t)(tl.first_tile + j) * 4 + (P - 1)) * 256 + tid];
+    hist[tid] = sum;
   }
   __syncthreads();
-  st.prefix |= (uint32_t)sh_digit << (24 - 8 * PASS);
-  st.need = sh_need;
-  st.digit[PASS] = sh_digit;
-  if (tid == 0) p.sel_state[tl.first_tile] = st;
-  if (PASS == 3) {
-    // survivors in front of each tile: rows outside the middle, keys that some pass ranked above the
-    // threshold's digit, keys equal to the threshold (capped by need where they are used)
-    constexpr int kChunk = 512;  // tiles whose counts are staged in LDS at a time
-    __shared__ int tile_sure[kChunk], tile_eq[kChunk];
-    int run_sure = 0, run_eq = 0;  // thread 0: totals over the tiles so far
-    for (int j0 = 0; j0 < tl.n_tiles; j0 += kChunk) {
-      const int nj = min(kChunk, tl.n_tiles - j0);
-      for (int j = wave; j < nj; j += 4) {  // one wavefront per tile: its 64 lanes cover the 256 counters
-        const int32_t* th = p.tile_hist + (int64_t)(tl.first_tile + j0 + j) * 4 * 256;
-        int sure = 0, eq = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int d = lane + 64 * q;
-#pragma unroll
-          for (int ps = 0; ps < 4; ++ps) sure += d > st.digit[ps] ? th[ps * 256 + d] : 0;
-          eq += d == st.digit[3] ? th[3 * 256 + d] : 0;
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-          sure += __shfl_xor(sure, o);
-          eq += __shfl_xor(eq, o);
-        }
-        if (lane == 0) { tile_sure[j] = sure; tile_eq[j] = eq; }
-      }
-      __syncthreads();
-      if (tid == 0) {
-        for (int j = 0; j < nj; ++j) {
-          p.tile_base_cnt[(int64_t)(tl.first_tile + j0 + j) * 2] = run_sure;
-          p.tile_base_cnt[(int64_t)(tl.first_tile + j0 + j) * 2 + 1] = run_eq;
-          run_sure += tile_sure[j];
-          run_eq += tile_eq[j];
-        }
-      }
-      __syncthreads();
-    }
-  }
+  find_digit(hist, st.need, sm_scan, sh_digit, sh_need);
+  st.prefix |= (uint32_t)*sh_digit << (24 - 8 * (P - 1));
+  st.need = *sh_need;
+  st.digit[P - 1] = *sh_digit;
+  __syncthreads();
+  if (tl.tile == 0 && tid == 0) p.sel_state[(int64_t)tl.long_idx * 4 + (P - 1)] = st;
+  return st;
 }
 
 template <int PASS>
@@ -338,13 +289,15 @@ __global__ __launch_bounds__(kSelThreads) void compact_tile_count_kernel(Compact
   }
   if (g.n <= g.b || g.k <= 0) return;  // nothing to rank (uniform over the cache's workgroups)
   __shared__ int hist[256];
-  const uint32_t prefix = PASS == 0 ? 0u : p.sel_state[tl.first_tile].prefix;
+  __shared__ int sm_scan[kSelWaves];
+  __shared__ int sh_digit, sh_need;
+  const SelState st = state_before_pass<PASS>(p, tl, g.k, hist, sm_scan, &sh_digit, &sh_need);
   for (int i = tid; i < 256; i += kSelThreads) hist[i] = 0;
   __syncthreads();
   const int shift = 24 - 8 * PASS;
   const uint32_t mask = PASS == 0 ? 0u : (0xffffffffu << (shift + 8));
   const int j_begin = max(g.mid_lo, tl.tile * kTileRows), j_end = min(g.mid_hi, (tl.tile + 1) * kTileRows);
-  count_digits<kTileRows / kSelThreads>(p.score + p.off[c], j_begin, j_end, prefix, mask, shift, hist);
+  count_digits<kTileRows / kSelThreads>(p.score + p.off[c], j_begin, j_end, st.prefix, mask, shift, hist);
   __syncthreads();
   if (tid < 256) p.tile_hist[((int64_t)(tl.first_tile + tl.tile) * 4 + PASS) * 256 + tid] = hist[tid];
 }
@@ -363,25 +316,40 @@ __global__ __launch_bounds__(kSelThreads) void compact_tile_emit_kernel(CompactP
       for (int j = j_begin + tid; j < j_end; j += kSelThreads) kept[j] = j;
     return;
   }
+  __shared__ int hist[256];
   __shared__ int sm_scan[kSelWaves];
-  __shared__ int sh_first;
+  __shared__ int sh_digit, sh_need, sh_first;
   __shared__ uint32_t lds_key[kEmitKeyWords];
-  __shared__ int32_t lds_out[kEmitTile];
   uint32_t thr = 0;
   int need_eq = 0, sure_base = 0, eq_base = 0;
   if (g.k > 0) {
-    const SelState st = p.sel_state[tl.first_tile];
+    const SelState st = state_before_pass<4>(p, tl, g.k, hist, sm_scan, &sh_digit, &sh_need);
     thr = st.prefix;
     need_eq = st.need;
-    sure_base = p.tile_base_cnt[(int64_t)(tl.first_tile + tl.tile) * 2];
-    eq_base = p.tile_base_cnt[(int64_t)(tl.first_tile + tl.tile) * 2 + 1];
+    // Survivors in the tiles before this one, from their counters: keys that some pass ranked above the
+    // threshold's digit, and keys equal to the threshold (capped by need_eq where they are used).
+    // One wavefront per earlier tile in turn, its 64 lanes over the 256 counters of each pass.
+    const int lane = tid & 63, wave = tid >> 6;
+    int sure = 0, eq = 0;
+    for (int j = wave; j < tl.tile; j += kSelWaves) {
+      const int32_t* th = p.tile_hist + (int64_t)(tl.first_tile + j) * 4 * 256;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int d = lane + 64 * q;
+#pragma unroll
+        for (int ps = 0; ps < 4; ++ps) sure += d > st.digit[ps] ? th[ps * 256 + d] : 0;
+        eq += d == st.digit[3] ? th[3 * 256 + d] : 0;
+      }
+    }
+    (void)block_exclusive_scan(sure, sm_scan, sure_base);
+    (void)block_exclusive_scan(eq, sm_scan, eq_base);
   }
   const int before = min(j_begin, n);  // rows in front of this tile
   sure_base += min(before, g.mid_lo) + max(0, before - g.mid_hi);
   if (tid == 0) sh_first = n;
   __syncthreads();
   if (j_begin < j_end)
-    emit_rows(p.score + off, kept, g, thr, need_eq, j_begin, j_end, sure_base, eq_base, sm_scan, &sh_first, lds_key, lds_out);
+    emit_rows(p.score + off, kept, g, thr, need_eq, j_begin, j_end, sure_base, eq_base, sm_scan, &sh_first, lds_key);
   __syncthreads();
   if (tid == 0 && sh_first < n) atomicMin(&p.info[c].first_moved, sh_first);
 }
@@ -511,19 +479,15 @@ __global__ __launch_bounds__(kMoveThreads) void compact_move_kernel(CompactParam
 
 }  // namespace
 
-hipError_t launch_compact_select(const CompactParams& p, int n_caches, int n_tiles, int n_long, hipStream_t s) {
+hipError_t launch_compact_select(const CompactParams& p, int n_caches, int n_tiles, hipStream_t s) {
   if (n_caches <= 0) return hipSuccess;
   compact_select_kernel<<<dim3(n_caches), dim3(kSelThreads), 0, s>>>(p);
   if (n_tiles > 0) {
-    const dim3 grid(n_tiles), block(kSelThreads), per_cache(n_long);
+    const dim3 grid(n_tiles), block(kSelThreads);
     compact_tile_count_kernel<0><<<grid, block, 0, s>>>(p);
-    compact_digit_kernel<0><<<per_cache, dim3(256), 0, s>>>(p);
     compact_tile_count_kernel<1><<<grid, block, 0, s>>>(p);
-    compact_digit_kernel<1><<<per_cache, dim3(256), 0, s>>>(p);
     compact_tile_count_kernel<2><<<grid, block, 0, s>>>(p);
-    compact_digit_kernel<2><<<per_cache, dim3(256), 0, s>>>(p);
     compact_tile_count_kernel<3><<<grid, block, 0, s>>>(p);
-    compact_digit_kernel<3><<<per_cache, dim3(256), 0, s>>>(p);
     compact_tile_emit_kernel<<<grid, block, 0, s>>>(p);
   }
   return hipGetLastError();

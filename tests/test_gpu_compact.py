@@ -192,6 +192,7 @@ def test_caches_selected_tile_by_tile(scores, policy):
     budgets = [8100, 8192, 8193, 20, 16300, 16384, 24581, 500]
     extra = [300, 1, 150, 77, 0, 300, 299, 37]
     arena = H.make_arena(w, budgets, policy=policy)
+    arena.set_option(B.OPT_TILED_SELECT_ROWS, 8192)       # the smallest threshold: six of the eight caches are tiled
     assert sum(1 for c in arena.cap_host if c > 8192) == 6
     lens = [b + e for b, e in zip(budgets, extra)]
     st = H.fill_from_host(arena, w, lens, rng, scores="uniform")

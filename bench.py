@@ -517,7 +517,8 @@ def measure_workload(args, name, torch, B, synth, np, want_full_eviction=True):
                 "value_with_eviction": round(main_r["kv_bytes_per_step"] / per_step_us / 1e3, 2), "unit": "GB/s",
                 "us_per_step_with_eviction": round(per_step_us, 1),
                 "pct_of_hbm_peak_with_eviction": round(100.0 * main_r["kv_bytes_per_step"] / per_step_us / 1e3 / HBM_PEAK_GBPS, 2),
-                "series_step_us": series,
+                "series_step_us": series if len(series) <= 24 else series[:6] + series[-12:],
+                "evictions_timed": len(series),
                 "note": "baklava_compact as the decode loop reaches it on schedule"
                         + (", scores accumulated by the attention kernel on top of the synthetic prompt scores" if tracked else "")
                         + "; `us` = median of the last three of the series; which rows leave, and hence how many move, follows from the scores",

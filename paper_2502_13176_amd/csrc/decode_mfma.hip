@@ -480,9 +480,13 @@ static_assert(kDynShared >= kWaves * kSlab * 4, "room for one slab of scores per
 
 // Called when a context is created on the current device, i.e. outside any stream capture: raises
 // the kernel's dynamic-LDS limit once, so that launches (captured or not) only launch.
+constexpr int kFlushDynMax = 48 * 1024;  // the flush kernel's share for waiting scores, beside its K staging area
 hipError_t prepare_decode_mfma() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma<true>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kDynMax);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_mfma<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kDynMax);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(score_flush_mfma),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kFlushDynMax);
 }
 
 hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_count, bool one_wave, hipStream_t s) {
@@ -510,7 +514,7 @@ hipError_t launch_score_flush_mfma(const DecodeParams& p_in, int n_items, int ma
   if (p_in.G > 16) return hipErrorInvalidValue;
   DecodeParams p = p_in;
   const int slot_bytes = kSlab * 4;
-  const int fit = (48 * 1024) / (kWaves * slot_bytes);  // beside the K staging area, within the default LDS limit
+  const int fit = kFlushDynMax / (kWaves * slot_bytes);
   const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;
   p.ring_slots = std::max(1, std::min(fit, need));
   score_flush_mfma<<<dim3(n_items), dim3(64 * kWaves), (size_t)p.ring_slots * kWaves * slot_bytes, s>>>(p);

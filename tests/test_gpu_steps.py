@@ -320,3 +320,109 @@ def test_256_step_trajectory_on_a_small_replica_of_the_long_workload():
         assert arena.lengths().tolist() == arena.len.cpu().tolist()
     print(f"256-step replica: worst attention error {worst[0]:.3e}, worst score error {worst[1]:.3e}", flush=True)
     arena.close()
+
+
+def test_records_survive_option_changes_and_are_dropped_with_the_rows():
+    """What the deferred score update has on record must come out right whatever happens between the
+    calls: the other attention kernel takes over (it first adds what is on record), tracking is paused
+    and resumed, a flush is repeated (the second one adds nothing), the work-item tables are rebuilt;
+    and baklava_set_lengths / baklava_reset drop records together with the rows they belong to."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["long"], name="rec", L=2, Hq=8, Hkv=2, batch=2, ctx=2048, lo=96, hi=2048,
+                     interval=64, slack=64, sink=4, recent=16, seed=88, floor_frac=0.0)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    budgets = synth.budgets_for(w, B.alloc_proportional)
+    arena = H.make_arena(w, budgets, track=True)
+    cpl = w.batch * w.Hkv
+    lens = [budgets[(c // cpl) * w.Hkv + c % w.Hkv] for c in range(arena.n_caches)]
+    st = H.fill_from_host(arena, w, lens, rng, scores="zero")
+    caches = [H.oracle_cache(w, st, c) for c in range(arena.n_caches)]
+    dev = arena.device
+    counted = 0                                            # calls whose weights the oracle has added
+
+    def call(track=True):
+        nonlocal counted
+        q, q64 = H.make_q(w, rng, w.L)
+        qd = H.to_device_storage(q, w.dtype, dev)
+        outd = torch.full((w.L, w.batch, w.Hq, w.D), float("nan"), dtype=torch.float32, device=dev)
+        for l in range(w.L):
+            arena.decode_attn(l, 1, qd[l], outd[l])
+        torch.cuda.synchronize()
+        out = outd.cpu().numpy().astype(np.float64)
+        for c in range(arena.n_caches):
+            l, b, hs = H.q_rows_of_cache(w, c)
+            ref, _, _ = O.decode_step(caches[c], q64[l, b, hs], None, None, 0, 0, 0, 0, 0, 0, track)
+            assert float(np.max(np.abs(out[l, b, hs] - ref))) <= H.ATTN_TOL
+        counted += 1 if track else 0
+
+    def check_scores(what):
+        post = H.download(arena, w)                        # flushes
+        for c in range(arena.n_caches):
+            serr = np.abs(post.score[c].astype(np.float64) - caches[c].score)
+            assert np.all((serr <= SCORE_TOL) | (serr <= SCORE_TOL * np.abs(caches[c].score))), f"{what}: cache {c}, {serr.max():.3e}"
+            assert abs(float(post.score[c].astype(np.float64).sum()) - w.G * counted) <= 1e-3, what
+
+    arena.set_option(B.OPT_KERNEL, B.KERNEL_MFMA)
+    call(); call(); call()                                 # three calls on record
+    arena.set_option(B.OPT_KERNEL, B.KERNEL_VALU)          # the other kernel adds them before its own
+    call()
+    raw = H.download(arena, w, flush=False)
+    for c in range(arena.n_caches):
+        assert abs(float(raw.score[c].astype(np.float64).sum()) - w.G * 4) <= 1e-3   # nothing owed after a vector-ALU call
+    arena.set_option(B.OPT_KERNEL, B.KERNEL_MFMA)
+    call(); call()
+    arena.set_option(B.OPT_TRACK_SCORES, 0)                # paused: these leave no record, the two before stay on it
+    call(track=False); call(track=False)
+    arena.set_option(B.OPT_TRACK_SCORES, 1)
+    call()
+    H.set_chunk(arena, 256)                                # new work-item tables: the records do not depend on them
+    arena.set_option(B.OPT_TARGET_ITEMS, 2)
+    call(); call(); call()                                 # the record fills up and is applied by a call
+    check_scores("after option changes")
+    arena.flush_scores(0, w.L)
+    arena.flush_scores(0, w.L)                             # nothing on record: adds nothing
+    check_scores("after repeated flushes")
+    # records are dropped with the rows they belong to
+    call(); call()
+    arena.set_lengths(lens)                                # the caller declares the rows anew: two calls' weights are gone
+    arena.score.zero_()
+    for c in range(arena.n_caches):
+        caches[c].score[:] = 0.0
+    counted = 0
+    call()
+    check_scores("after set_lengths")
+    call()
+    arena.reset()
+    torch.cuda.synchronize()
+    assert arena.lengths().tolist() == [0] * arena.n_caches
+    arena.set_lengths(lens)
+    arena.score.zero_()
+    for c in range(arena.n_caches):
+        caches[c].score[:] = 0.0
+    counted = 0
+    call(); call()
+    check_scores("after reset")
+    arena.close()
+
+
+def test_tiled_selection_threshold_does_not_change_the_result():
+    """The same eviction with every cache ranked by one workgroup and with the long ones ranked tile by
+    tile: identical lists and rows."""
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama32"], name="thr", L=1, Hq=4, Hkv=4, batch=1, seed=89, sink=4, recent=64, slack=500)
+    budgets = [12000, 40000, 9000, 300]
+    results = []
+    for rows in (1 << 30, 8192, 16384):
+        rng = np.random.Generator(np.random.PCG64(w.seed))
+        arena = H.make_arena(w, budgets)
+        arena.set_option(B.OPT_TILED_SELECT_ROWS, rows)
+        lens = [b + 500 - 37 * i for i, b in enumerate(budgets)]
+        st = H.fill_from_host(arena, w, lens, rng, scores="uniform")
+        kept_dev = torch.full((arena.total_tokens,), -1, dtype=torch.int32, device=arena.device)
+        arena.compact(0, 1, kept_dev)
+        torch.cuda.synchronize()
+        after = H.download(arena, w)
+        H.check_eviction_against_oracle(arena, w, budgets, st, after, kept_dev, range(arena.n_caches))
+        results.append(kept_dev.cpu().numpy())
+        arena.close()
+    assert np.array_equal(results[0], results[1]) and np.array_equal(results[0], results[2])

@@ -283,7 +283,7 @@ int baklava_sync_lengths(baklava_ctx* ctx, void* stream);
  * heavy-hitter policies the paper's Related Work cites).  A row's weight in a call needs the
  * softmax normaliser of its whole cache, which is only known when the call is over, so the weights
  * of a call are added by a later attention call over the same layer, which streams the same K
- * rows anyway (a cache keeps up to 4 calls on record and adds them together), or by this
+ * rows anyway (a cache keeps up to 8 calls on record and adds them together), or by this
  * function: a pass over the K rows of the layer range alone.  After it the score plane of the
  * range holds every weight up to the latest call; without it the plane lacks at most the weights
  * of the calls on record, never anything else.  baklava_compact does this itself before it ranks

@@ -101,12 +101,12 @@ WorkspacePlan plan_workspace(const baklava_desc* d, const int32_t* cap, const in
   w.part_o = o;       o = align256(o + (size_t)w.max_items * G * d->D * 4);
   w.part_ml = o;      o = align256(o + (size_t)w.max_items * G * 2 * 4);
   w.final_ml = o;     o = align256(o + (size_t)n_caches * G * 2 * 4);
-  // the record of the pending calls of every cache (score tracking): 16 packed query rows, their
+  // the record of the pending calls of every cache (score tracking): 32 packed query rows, their
   // (max, 1/sum), the rows each call saw, the count of pending calls per head
   const bool track = d->track_scores != 0;
-  w.lag_q = o;        o = align256(o + (track ? (size_t)n_caches * 16 * row_bytes : 0));
-  w.lag_ml = o;       o = align256(o + (track ? (size_t)n_caches * 16 * 2 * 4 : 0));
-  w.lag_n = o;        o = align256(o + (size_t)n_caches * 4 * 4);
+  w.lag_q = o;        o = align256(o + (track ? (size_t)n_caches * kLagRows * row_bytes : 0));
+  w.lag_ml = o;       o = align256(o + (track ? (size_t)n_caches * kLagRows * 2 * 4 : 0));
+  w.lag_n = o;        o = align256(o + (size_t)n_caches * kLagCalls * 4);
   w.lag_cnt = o;      o = align256(o + (size_t)n_caches * G * 4);
   w.status = o;       o = align256(o + 256);
   w.kept = o;         o = align256(o + (size_t)total_tokens * 4);
@@ -342,7 +342,7 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
   p.G = ctx->G; p.Hq = ctx->d.Hq; p.Hkv = ctx->d.Hkv; p.batch = ctx->d.batch;
   p.cache_begin = (int32_t)c0;
   p.lag = (track && use_mfma) ? 1 : 0;
-  p.lag_batch = 16 >> ctx->lag_gp_log2 > 4 ? 4 : 16 >> ctx->lag_gp_log2;
+  p.lag_batch = kLagRows >> ctx->lag_gp_log2;
   p.lag_gp_log2 = ctx->lag_gp_log2;
   p.ring_slots = 0;
   p.fused_append = fused ? 1 : 0;

@@ -20,6 +20,8 @@ __device__ __forceinline__ void store_nt16(void* ptr, uint4 v) {
 }
 #endif
 
+constexpr int kLagRows = 32;   // packed query rows of a cache's record of pending calls (score tracking)
+constexpr int kLagCalls = 8;   // most calls such a record holds
 constexpr int kMoveSegRows = 4096;  // destination rows per workgroup of the eviction move
 constexpr int kTileRows = 8192;     // rows per tile of a cache that is ranked tile by tile (one workgroup per tile and pass)
 constexpr int kMinLongRows = kTileRows;  // smallest capacity from which a cache may be ranked that way
@@ -78,13 +80,13 @@ struct DecodeParams {
   // Score tracking, MFMA kernel: the weights of a call are added to the score plane by a later
   // call over the same caches (or by the score pass that baklava_flush_scores launches), because
   // only then are the softmax normalisers known to every work item.  Each cache keeps a record of
-  // up to lag_batch pending calls; their query rows are packed into one 16-row operand (call s,
-  // head g -> row s * Gp + g, Gp = G rounded up to 4, 8 or 16), so that one extra matrix product
-  // per slab serves all of them.  A call that finds lag_batch calls pending adds their weights and
-  // starts the record again with itself.
-  void* lag_q;                     // [n_caches, 16, D] packed query rows of the pending calls
-  float* lag_ml;                   // [n_caches, 16, 2] their (max, 1 / sum), same row numbering
-  int32_t* lag_n;                  // [n_caches, 4] rows that were live at pending call s
+  // up to lag_batch pending calls; their query rows are packed into two 16-row operands (call s,
+  // head g -> packed row s * Gp + g, Gp = G rounded up to 4, 8 or 16), so that two extra matrix
+  // products per slab serve all of them.  A call that finds lag_batch calls pending adds their
+  // weights and starts the record again with itself.
+  void* lag_q;                     // [n_caches, kLagRows, D] packed query rows of the pending calls
+  float* lag_ml;                   // [n_caches, kLagRows, 2] their (max, 1 / sum), same row numbering
+  int32_t* lag_n;                  // [n_caches, kLagCalls] rows that were live at pending call s
   int32_t* lag_cnt;                // [n_caches, G] pending calls (one counter per head, all equal:
                                    // each block of the combine kernel reads and writes its own)
   const int32_t* cap;
@@ -98,7 +100,7 @@ struct DecodeParams {
   int32_t G, Hq, Hkv, batch;
   int32_t cache_begin;             // first cache id of the launched range
   int32_t lag;                     // 1: record this call, apply the pending ones when due (MFMA kernel)
-  int32_t lag_batch;               // calls a record holds: 16 / Gp, at most 4
+  int32_t lag_batch;               // calls a record holds: kLagRows / Gp
   int32_t lag_gp_log2;             // log2(Gp)
   int32_t ring_slots;              // MFMA kernel, lag: slabs per wavefront whose new scores wait in LDS
   int32_t fused_append;            // 1: every cache of the range first receives its new row

@@ -31,8 +31,8 @@
 // later call -- whose K rows pass through LDS anyway -- forms the recorded calls' logits with one
 // more product that reuses the K operands (the matrix pipe is < 10% busy), turns them into
 // normalised weights and adds them to the scores.  The G query heads fill only G of the 16 rows of
-// a matrix operand, so the rows of up to 16 / G recorded calls are packed into one operand and
-// the scores are touched only on every (16 / G)-th call (at most every 4th).  On such a call the
+// a matrix operand, so the rows of up to 32 / G recorded calls are packed into two operands and
+// the scores are touched only on every (32 / G)-th call (every 8th at G <= 4).  On such a call the
 // scores of a slab are read with the slab and the new values wait in LDS until the work item is
 // done, so the extra HBM writes (4 bytes per row) fall at the end of a launch instead of between
 // the K/V reads.
@@ -69,57 +69,70 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(u32x4_t x) { return __builtin_bit_cast(bf16x8_t, x); }
 
-// The recorded calls of one cache as a lane sees them.  The packed query rows are the A operand of
-// the product S' = Q' K^T (lane (m, j), chunk c holds row m, elements 32c + 8j .. +8); the product
-// leaves lane (row, jg) with the logits of packed rows 4*jg .. 4*jg+3, which all belong to one
-// call, so the lane keeps their (max, 1/sum) and the number of rows that call saw.
+// The recorded calls of one cache as a lane sees them.  The packed query rows fill kSets operands
+// of 16 rows (packed row R = call * G' + head sits in operand R / 16, row R % 16); each is the A
+// operand of a product S' = Q' K^T (lane (m, j), chunk c holds row m, elements 32c + 8j .. +8) that
+// leaves lane (row, jg) with the logits of the operand's rows 4*jg .. 4*jg+3, which all belong to
+// one call, so the lane keeps their (max, 1/sum) and the number of rows that call saw.
+constexpr int kSets = 2;
+constexpr int kRecRows = 16 * kSets;  // packed rows of a record
+constexpr int kRecCalls = 8;          // most calls a record holds (G <= 4)
 struct Record {
-  bf16x8_t q[4];
-  float m[4], inv[4];
-  int n_slot;
+  bf16x8_t q[kSets][4];
+  float m[kSets][4], inv[kSets][4];
+  int n_slot[kSets];
 };
 
 __device__ __forceinline__ void load_record(const DecodeParams& p, int c, int G, int pending, int n16, int jg,
                                             Record& r) {
   const int gp_mask = (1 << p.lag_gp_log2) - 1;
-  const unsigned char* lq = reinterpret_cast<const unsigned char*>(p.lag_q) + (int64_t)c * 16 * (kD * 2);
+  const unsigned char* lq = reinterpret_cast<const unsigned char*>(p.lag_q) + (int64_t)c * kRecRows * (kD * 2);
 #pragma unroll
-  for (int ch = 0; ch < 4; ++ch) {
-    u32x4_t raw = {0u, 0u, 0u, 0u};  // rows beyond the G heads of a call, calls not on record: zero
-    if ((n16 & gp_mask) < G && (n16 >> p.lag_gp_log2) < pending)
-      raw = *reinterpret_cast<const u32x4_t*>(lq + n16 * (kD * 2) + ch * 64 + jg * 16);
-    r.q[ch] = as_bf16x8(raw);
-  }
-  const int slot = (4 * jg) >> p.lag_gp_log2;
-  r.n_slot = 0;
-  if (slot < pending) r.n_slot = p.lag_n[(int64_t)c * 4 + slot];
+  for (int e = 0; e < kSets; ++e) {
+    const int R = 16 * e + n16;  // the packed row this lane holds a part of
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = 4 * jg + i;
-    r.m[i] = 0.f;
-    r.inv[i] = 0.f;
-    if ((m & gp_mask) < G && slot < pending) {
-      r.m[i] = p.lag_ml[((int64_t)c * 16 + m) * 2];
-      r.inv[i] = p.lag_ml[((int64_t)c * 16 + m) * 2 + 1];
+    for (int ch = 0; ch < 4; ++ch) {
+      u32x4_t raw = {0u, 0u, 0u, 0u};  // rows beyond the G heads of a call, calls not on record: zero
+      if ((R & gp_mask) < G && (R >> p.lag_gp_log2) < pending)
+        raw = *reinterpret_cast<const u32x4_t*>(lq + R * (kD * 2) + ch * 64 + jg * 16);
+      r.q[e][ch] = as_bf16x8(raw);
+    }
+    const int slot = (16 * e + 4 * jg) >> p.lag_gp_log2;
+    r.n_slot[e] = 0;
+    if (slot < pending) r.n_slot[e] = p.lag_n[(int64_t)c * kRecCalls + slot];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = 16 * e + 4 * jg + i;
+      r.m[e][i] = 0.f;
+      r.inv[e][i] = 0.f;
+      if ((m & gp_mask) < G && slot < pending) {
+        r.m[e][i] = p.lag_ml[((int64_t)c * kRecRows + m) * 2];
+        r.inv[e][i] = p.lag_ml[((int64_t)c * kRecRows + m) * 2 + 1];
+      }
     }
   }
 }
 
 // Weights the recorded calls give to the 32 rows of a slab whose first row has cache index `row_first`:
-// sum over calls and heads of 2^(s' - M') / L' for the rows a call saw.  sp[T] holds the logits of
-// tile T as the product left them.  On return lane l < 32 holds the weight of row l of the slab.
-__device__ __forceinline__ float record_weights(const floatx4_t (&sp)[2], const Record& r, float cs,
+// sum over calls and heads of 2^(s' - M') / L' for the rows a call saw.  sp[e][T] holds the logits of
+// operand e and tile T as the product left them.  On return lane l < 32 holds the weight of row l of
+// the slab.
+__device__ __forceinline__ float record_weights(const floatx4_t (&sp)[kSets][2], const Record& r, float cs,
                                                 int row_first, int lane) {
   const int n16 = lane & 15;
   float w[2];
 #pragma unroll
   for (int T = 0; T < 2; ++T) {
-    float acc = 0.f;
+    w[T] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc += fast_exp2(sp[T][i] * cs - r.m[i]) * r.inv[i];
-    // a row the call did not see is left out by a select: its logit may be anything
-    w[T] = (row_first + T * 16 + n16 < r.n_slot) ? acc : 0.f;
-    w[T] += __shfl_xor(w[T], 16);  // packed rows 4*jg .. 4*jg+3 sit in lane group jg
+    for (int e = 0; e < kSets; ++e) {
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc += fast_exp2(sp[e][T][i] * cs - r.m[e][i]) * r.inv[e][i];
+      // a row the call did not see is left out by a select: its logit may be anything
+      w[T] += (row_first + T * 16 + n16 < r.n_slot[e]) ? acc : 0.f;
+    }
+    w[T] += __shfl_xor(w[T], 16);  // an operand's rows 4*jg .. 4*jg+3 sit in lane group jg
     w[T] += __shfl_xor(w[T], 32);
   }
   return (lane & 16) ? w[1] : w[0];
@@ -265,11 +278,12 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // ---- S^T = K Q^T: lane (row%16, j) reads elements 32c + 8j .. +8 of its row ----------------
-    floatx4_t s[2], sp[2];
+    floatx4_t s[2], sp[kSets][2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
       s[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-      sp[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int e = 0; e < kSets; ++e) sp[e][T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const u32x4_t a = *reinterpret_cast<const u32x4_t*>(myk + (T * 16 + n16) * kKStride + c * 64 + jg * 16);
@@ -277,7 +291,11 @@ __global__ __launch_bounds__(64 * kWaves, BAKLAVA_MFMA_WAVES_PER_EU) void decode
         // The same K registers are a valid B operand (lane (row, j): elements 32c + 8j .. +8 of its
         // row), so S' = Q' K^T costs no further LDS read: lane (row, jg) receives the pending
         // call's logits of heads 4*jg .. 4*jg+3 for row 16T + row of the slab.
-        if (APPLY) sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
+        if (APPLY) {
+#pragma unroll
+          for (int e = 0; e < kSets; ++e)
+            sp[e][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[e][c], as_bf16x8(a), sp[e][T], 0, 0, 0);
+        }
       }
     }
 
@@ -401,8 +419,8 @@ __global__ __launch_bounds__(64 * kWaves) void score_flush_mfma(DecodeParams p) 
   const int pending = p.lag_cnt[(int64_t)it.c * G];
   if (pending == 0) return;
   int n_seen = 0;  // rows the latest recorded call saw: no earlier one saw more
-  for (int s = 0; s < 4; ++s)
-    if (s < pending) n_seen = max(n_seen, p.lag_n[(int64_t)it.c * 4 + s]);
+  for (int s = 0; s < kRecCalls; ++s)
+    if (s < pending) n_seen = max(n_seen, p.lag_n[(int64_t)it.c * kRecCalls + s]);
   const int cnt = min(it.start + it.count, n_seen) - it.start;
   if (cnt <= 0) return;
   Record rec;
@@ -447,14 +465,17 @@ __global__ __launch_bounds__(64 * kWaves) void score_flush_mfma(DecodeParams p) 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    floatx4_t sp[2];
+    floatx4_t sp[kSets][2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
-      sp[T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int e = 0; e < kSets; ++e) sp[e][T] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const u32x4_t a = *reinterpret_cast<const u32x4_t*>(myk + (T * 16 + n16) * kKStride + c * 64 + jg * 16);
-        sp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[c], as_bf16x8(a), sp[T], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < kSets; ++e)
+          sp[e][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(rec.q[e][c], as_bf16x8(a), sp[e][T], 0, 0, 0);
       }
     }
     const float wr = record_weights(sp, rec, cs, it.start + t0, lane);

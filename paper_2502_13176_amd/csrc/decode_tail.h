@@ -76,7 +76,7 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
         p.final_ml[((int64_t)c * G + g) * 2 + 1] = inv;
         if (p.lag) {
           const int slot = lag_slot(p, p.lag_cnt[(int64_t)c * G + g]);
-          const int64_t m = (int64_t)c * 16 + (slot << p.lag_gp_log2) + g;
+          const int64_t m = (int64_t)c * kLagRows + (slot << p.lag_gp_log2) + g;
           p.lag_ml[m * 2 + 0] = ms;
           p.lag_ml[m * 2 + 1] = inv;
         }
@@ -100,10 +100,10 @@ __device__ __forceinline__ void finish_item(const DecodeParams& p, const Item& i
     const int ppr = p.row_bytes / 16;  // 16-byte pieces per row
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) + orow0 * p.row_bytes);
     uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<char*>(p.lag_q) +
-                                          ((int64_t)c * 16 + (slot << p.lag_gp_log2)) * p.row_bytes);
+                                          ((int64_t)c * kLagRows + (slot << p.lag_gp_log2)) * p.row_bytes);
     for (int i = tid; i < G * ppr; i += 64 * NW) dst[i] = src[i];
     __syncthreads();
-    if (tid == 0) p.lag_n[(int64_t)c * 4 + slot] = n_new;
+    if (tid == 0) p.lag_n[(int64_t)c * kLagCalls + slot] = n_new;
     if (tid < G) p.lag_cnt[(int64_t)c * G + tid] = slot + 1;
   }
 }

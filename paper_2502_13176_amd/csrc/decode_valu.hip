@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
     // This head's part of the record a later score pass over the cache needs (see DecodeParams).
     // Each block reads and writes the pending-call counter of its own head only.
     if (p.lag) {
-      const int64_t m = (int64_t)c * 16 + (slot << p.lag_gp_log2) + g;
+      const int64_t m = (int64_t)c * kLagRows + (slot << p.lag_gp_log2) + g;
       if (tid * 16 < p.row_bytes) {
         const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) + orow * p.row_bytes);
         reinterpret_cast<uint4*>(reinterpret_cast<char*>(p.lag_q) + m * p.row_bytes)[tid] = src[tid];
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void combine_kernel(DecodeParams p) {
       if (d == 0) {
         p.lag_ml[m * 2 + 0] = ms;
         p.lag_ml[m * 2 + 1] = inv;
-        if (g == 0) p.lag_n[(int64_t)c * 4 + slot] = n_now;
+        if (g == 0) p.lag_n[(int64_t)c * kLagCalls + slot] = n_now;
         p.lag_cnt[(int64_t)c * G + g] = slot + 1;
       }
     }

@@ -128,7 +128,7 @@ LAG_CASES = [("long", 8, 2, 2, 0, True), ("long", 8, 2, 2, 3, False), ("qwen", 7
 def test_deferred_score_updates_over_windows_of_steps(base, Hq, Hkv, batch, target, fused):
     H = _h()
     w = synth.shrink(synth.WORKLOADS[base], name="lag", L=2, Hq=Hq, Hkv=Hkv, batch=batch, ctx=2048, lo=96,
-                     hi=2048, interval=6, slack=6, sink=4, recent=16, steps=18 if batch < 9 else 12, floor_frac=0.0,
+                     hi=2048, interval=10, slack=10, sink=4, recent=16, steps=30 if batch < 9 else 20, floor_frac=0.0,
                      seed=77 + Hq)
     rng = np.random.Generator(np.random.PCG64(w.seed))
     budgets = synth.budgets_for(w, B.alloc_proportional)
@@ -176,8 +176,8 @@ def test_deferred_score_updates_over_windows_of_steps(base, Hq, Hkv, batch, targ
                 assert err <= H.ATTN_TOL, f"step {t} cache {c}: attention error {err:.3e}"
                 worst_out = max(worst_out, err)
         # without a flush the plane lacks the weights of the calls still on record, and only those: a record
-        # holds 16 / (G rounded up to 4, 8 or 16) calls, at most 4, and the call that finds it full empties it
-        room = min(4, 16 // (4 if w.G <= 4 else 8 if w.G <= 8 else 16))
+        # holds 32 / (G rounded up to 4, 8 or 16) calls, and the call that finds it full empties it
+        room = 32 // (4 if w.G <= 4 else 8 if w.G <= 8 else 16)
         on_record = 0
         for _ in range(w.interval):
             on_record = 1 if on_record >= room else on_record + 1
@@ -377,7 +377,8 @@ def test_records_survive_option_changes_and_are_dropped_with_the_rows():
     call()
     H.set_chunk(arena, 256)                                # new work-item tables: the records do not depend on them
     arena.set_option(B.OPT_TARGET_ITEMS, 2)
-    call(); call(); call()                                 # the record fills up and is applied by a call
+    for _ in range(9):                                     # the record (8 calls at G = 4) fills up and a call applies it
+        call()
     check_scores("after option changes")
     arena.flush_scores(0, w.L)
     arena.flush_scores(0, w.L)                             # nothing on record: adds nothing

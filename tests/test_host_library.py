@@ -134,9 +134,9 @@ def test_workspace_bytes_is_a_pure_host_query():
     n0 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
     d.track_scores = 1
     n1 = B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p))
-    # score tracking adds, per cache, 16 packed query rows and (max, 1/sum) pairs of its pending calls
+    # score tracking adds, per cache, 32 packed query rows and (max, 1/sum) pairs of its pending calls
     n_caches = w.L * w.batch * w.Hkv
-    lag_q, lag_ml = n_caches * 16 * w.D * 2, n_caches * 16 * 2 * 4
+    lag_q, lag_ml = n_caches * 32 * w.D * 2, n_caches * 32 * 2 * 4
     assert n0 > 0 and n1 == n0 + ((lag_q + 255) // 256) * 256 + ((lag_ml + 255) // 256) * 256
     d.D = 96
     assert B.lib().baklava_workspace_bytes(C.byref(d), cap.ctypes.data_as(i32p), bud.ctypes.data_as(i32p)) == 0

@@ -161,8 +161,9 @@ typedef struct {
 
 /*
  * Bytes of device workspace a context with this description needs (split partials, work-item
- * tables, kept-index lists, halo rows of the eviction move, and with track_scores the query rows
- * and softmax normalisers of each cache's latest attention call).  Pointer fields of `desc` are ignored.  cap_host HOST [n_caches],
+ * tables, kept-index lists, halo rows of the eviction move, the counters of the tile-by-tile
+ * selection, and with track_scores the query rows and softmax normalisers of the attention calls
+ * each cache has on record).  Pointer fields of `desc` are ignored.  cap_host HOST [n_caches],
  * budget_host HOST [L*Hkv].  Returns 0 on invalid arguments.
  */
 size_t baklava_workspace_bytes(const baklava_desc* desc, const int32_t* cap_host,
@@ -323,9 +324,10 @@ int baklava_compact(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count,
  * h / (Hq/Hkv)); all 16-byte aligned.  D must be 128 and dtype BAKLAVA_BF16.
  * cos_out DEVICE fp32 [batch, Hq, T] (per-token cosines) or NULL; sim_out DEVICE fp32 [batch, Hq]
  * (mean per head); lse_out DEVICE fp32 [batch, Hq, T] or NULL: per token, log2 of the sum over its
- * visible keys of 2^(q_t.k_j log2(e)/sqrt(D)), the softmax normaliser baklava_prefill_scores needs.  A cosine whose norm product is below 1e-8 is divided by 1e-8 instead (a zero
- * row gives 0).  workspace DEVICE, at least baklava_profile_workspace_bytes(batch, Hq, T) bytes,
- * 16-byte aligned, owned by the caller and free again once the stream has passed the call.
+ * visible keys of 2^(q_t.k_j log2(e)/sqrt(D)), the softmax normaliser baklava_prefill_scores needs.
+ * A cosine whose norm product is below 1e-8 is divided by 1e-8 instead (a zero row gives 0).
+ * workspace DEVICE, at least baklava_profile_workspace_bytes(batch, Hq, T) bytes, 16-byte aligned,
+ * owned by the caller and free again once the stream has passed the call.
  * Enqueues two kernels on `stream`, does not synchronise.  Results are deterministic.
  * Errors: EINVAL (null, misaligned, bad shape), ECAPACITY (workspace too small), EHIP.
  */
@@ -444,7 +446,6 @@ int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launch
  * Errors: EINVAL (null, misaligned, bytes not a positive multiple of 16, bad mode), EHIP.
  */
 int baklava_stream_probe(void* dst, const void* src, int64_t bytes, int32_t mode, void* stream);
-
 
 #ifdef __cplusplus
 }

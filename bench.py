@@ -30,7 +30,10 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=128)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=576,
+                    help="untimed steps of the same decode loop before the timed region (default 576: nine evictions at "
+                         "an interval of 64, eighteen at 32, after which an eviction costs what it costs in a long "
+                         "generation; the first ones after the synthetic start move nearly every row)")
     ap.add_argument("--workload", default="llama32", choices=["tiny", "llama1", "llama32", "qwen", "long"])
     ap.add_argument("--mode", default="layer", choices=["layer", "stack"],
                     help="layer: one attention launch per layer (as a model would issue them); "
@@ -47,6 +50,9 @@ def parse_args():
     ap.add_argument("--no-track", action="store_true", help="never accumulate attention scores")
     ap.add_argument("--no-second-workload", action="store_true",
                     help="skip the row of the second model shape (qwen beside llama32)")
+    ap.add_argument("--event-mode", type=int, default=2, choices=(1, 2),
+                    help="how the roofline region times the attention kernel: 1 = events recorded on the stream "
+                         "before and after each launch, 2 = events carried by the kernel's own dispatch")
     ap.add_argument("--evictions", type=int, default=10, help="evictions of the decode loop to time (see `eviction`)")
     ap.add_argument("--emit-row", action="store_true",
                     help="print only this workload's row (how the second workload is measured: in a process of its own)")
@@ -429,11 +435,12 @@ def measure_workload(args, name, torch, B, synth, np, want_full_eviction=True):
 
     def region(n_steps, mode, time_kernel=False):
         """n_steps decode steps bracketed by synchronisation; with time_kernel every attention launch is
-        also bracketed by HIP events on the launch stream."""
+        also timed with HIP events on the launch stream (--event-mode)."""
         align(n_steps, mode)
-        arena.set_option(B.OPT_TIME_KERNEL, 1 if time_kernel else 0)
+        arena.set_option(B.OPT_TIME_KERNEL, args.event_mode if time_kernel else 0)
         st["kv_bytes"] = 0
         st["evictions"] = 0
+        t_first = st["t"] + 1
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n_steps):
@@ -448,14 +455,16 @@ def measure_workload(args, name, torch, B, synth, np, want_full_eviction=True):
              "pct_of_hbm_peak": round(100.0 * st["kv_bytes"] / elapsed / 1e9 / HBM_PEAK_GBPS, 2),
              "kv_bytes_per_step": st["kv_bytes"] // n_steps}
         r["_elapsed"], r["_kv_bytes"], r["_kernel_ms"], r["_launches"] = elapsed, st["kv_bytes"], kernel_ms, launches
+        r["_t_first"], r["_t_last"] = t_first, st["t"]
         return r
 
     for _ in range(args.warmup):
         step(args.mode)
     # The timed region: exactly `steps` steps, nothing else on the stream.
     main_r = region(args.steps, args.mode)
-    # The same region again with event brackets around every attention launch: the brackets cost a few
-    # microseconds of stream time each, so they stay out of the region `value` comes from.
+    # The same region again with a pair of HIP events per attention launch (by default carried by the
+    # kernel's own dispatch, so that they take its start and end): timing a launch costs stream time, so
+    # this stays out of the region `value` comes from.
     roof_r = region(min(args.steps, 64), args.mode, time_kernel=True)
     other = "stack" if args.mode == "layer" else "layer"
     other_r = None if args.no_other_mode else region(min(args.steps, 32), other)
@@ -484,6 +493,8 @@ def measure_workload(args, name, torch, B, synth, np, want_full_eviction=True):
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
             "launches": int(launches), "avg_launch_us": round(avg_launch_s * 1e6, 2),
+            "timed_with": "HIP events carried by the kernel's dispatch" if args.event_mode == 2
+                          else "HIP events recorded on the stream before and after each launch",
             "algorithmic_bytes_per_launch": int(avg_launch_bytes),
         },
     }
@@ -510,10 +521,15 @@ def measure_workload(args, name, torch, B, synth, np, want_full_eviction=True):
         if series:
             tail = sorted(us for _, us in series[-3:])
             med = tail[len(tail) // 2]
-            per_step_us = main_r["us_per_step"] + med / interval
+            # the step time without evictions: those that fell into the timed region are taken out again
+            inside = sum(e[2].elapsed_time(e[3]) * 1e3 for e in eviction_events
+                         if main_r["_t_first"] <= e[0] <= main_r["_t_last"])
+            base_us = main_r["us_per_step"] - inside / main_r["steps"]
+            per_step_us = base_us + med / interval
             row["eviction"] = {
                 "us": med, "interval_steps": interval,
                 "amortised_us_per_step": round(med / interval, 2),
+                "us_per_step_without_eviction": round(base_us, 1),
                 "value_with_eviction": round(main_r["kv_bytes_per_step"] / per_step_us / 1e3, 2), "unit": "GB/s",
                 "us_per_step_with_eviction": round(per_step_us, 1),
                 "pct_of_hbm_peak_with_eviction": round(100.0 * main_r["kv_bytes_per_step"] / per_step_us / 1e3 / HBM_PEAK_GBPS, 2),

@@ -192,7 +192,11 @@ enum {
                                    the layers (multiple of 64, >= 256); the item target below may
                                    lengthen it                                                        */
   BAKLAVA_OPT_KERNEL = 2,       /* 0 = automatic, 1 = vector-ALU kernel, 2 = MFMA kernel (bf16, D=128) */
-  BAKLAVA_OPT_TIME_KERNEL = 3,  /* 1: bracket every attention partial-kernel launch with HIP events  */
+  BAKLAVA_OPT_TIME_KERNEL = 3,  /* time every attention partial-kernel launch with a pair of HIP events
+                                   (baklava_profile_read): 1 = recorded on the stream before and
+                                   after the launch, 2 = carried by the kernel's own dispatch (MFMA
+                                   kernel; the other kernel is timed as under 1), 0 = off.  ESTATE
+                                   while timings taken in another mode are still unread            */
   BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* the same for launches over all layers at once               */
   BAKLAVA_OPT_TARGET_ITEMS = 5, /* > 0: launches over part of the layers lengthen their runs, layer by
                                    layer, until a layer has at most this many work items; 0: off.
@@ -428,10 +432,12 @@ int baklava_lengths(baklava_ctx* ctx, int32_t* len_host_out);
 
 /*
  * Timing of the dominant kernel (the split-K attention partial kernel, which reads all
- * of the K/V bytes of Eq. 7): with BAKLAVA_OPT_TIME_KERNEL set, baklava_decode_attn records a HIP
- * event on the caller's stream right before and right after that kernel.  This call waits for
- * the recorded events, returns the summed elapsed time and the number of launches since the last
- * read, and clears the record.  total_ms_out, launches_out HOST scalars.
+ * of the K/V bytes of Eq. 7): with BAKLAVA_OPT_TIME_KERNEL set, every attention call takes a pair
+ * of HIP events for that kernel on the caller's stream: recorded right before and right after the
+ * launch (mode 1: the pair also spans what the stream does between two commands), or handed to
+ * the launch itself so that they carry the time stamps of the kernel's start and end (mode 2).
+ * This call waits for the events, returns the summed elapsed time and the number of launches since
+ * the last read, and clears the record.  total_ms_out, launches_out HOST scalars.
  */
 int baklava_profile_read(baklava_ctx* ctx, double* total_ms_out, int64_t* launches_out);
 

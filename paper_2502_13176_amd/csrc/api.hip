@@ -162,7 +162,7 @@ struct baklava_ctx {
   } sched[2];                          // 0: layer sub-range launches, 1: whole-model launches
   WorkspacePlan plan;
   char* ws;
-  bool time_kernel;
+  int32_t time_kernel;         // 0 off, 1 events recorded around the attention kernel, 2 events carried by its dispatch
   bool track_on;               // score tracking in force (BAKLAVA_OPT_TRACK_SCORES pauses it)
   std::vector<hipEvent_t> ev;  // pairs (before, after); the first 2 * ev_used are recorded
   size_t ev_used;
@@ -358,15 +358,17 @@ int decode_impl(baklava_ctx* ctx, int32_t layer_begin, int32_t layer_count, cons
     }
     ev0 = ctx->ev[2 * ctx->ev_used];
     ev1 = ctx->ev[2 * ctx->ev_used + 1];
-    if (!hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
+    if (!(ctx->time_kernel == 2 && use_mfma) && !hip_ok(hipEventRecord(ev0, s))) return BAKLAVA_EHIP;
   }
+  const bool on_dispatch = ctx->time_kernel == 2 && use_mfma;
   const int32_t longest = *std::max_element(sc.max_count.begin() + layer_begin,
                                             sc.max_count.begin() + layer_begin + layer_count);
-  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, longest, i1 - i0 <= ctx->n_cus, s)
+  hipError_t e = use_mfma ? launch_decode_mfma(p, i1 - i0, longest, i1 - i0 <= ctx->n_cus, s,
+                                               on_dispatch ? ev0 : nullptr, on_dispatch ? ev1 : nullptr)
                           : launch_decode_valu(p, ctx->d.dtype, ctx->d.D, i1 - i0, s);
   if (!hip_ok(e)) return BAKLAVA_EHIP;
   if (ctx->time_kernel) {
-    if (!hip_ok(hipEventRecord(ev1, s))) return BAKLAVA_EHIP;
+    if (!on_dispatch && !hip_ok(hipEventRecord(ev1, s))) return BAKLAVA_EHIP;
     ctx->ev_used += 1;
   }
   if (!hip_ok(launch_combine(p, ctx->d.D, m1 - m0, s))) return BAKLAVA_EHIP;
@@ -451,7 +453,7 @@ extern "C" int baklava_create(const baklava_desc* desc, const int64_t* off_host,
     // the dispatcher to even out the load over several waves of workgroups.
     ctx->target_items_whole = kWholeItemsPerCu * cus;
   }
-  ctx->time_kernel = false;
+  ctx->time_kernel = 0;
   ctx->track_on = desc->track_scores != 0;
   ctx->ev_used = 0;
   ctx->plan = plan_workspace(desc, cap_host, budget_host);
@@ -566,8 +568,9 @@ extern "C" int baklava_set_option(baklava_ctx* ctx, int32_t option, int64_t valu
       ctx->track_on = value == 1;
       return BAKLAVA_OK;
     case BAKLAVA_OPT_TIME_KERNEL:
-      if (value != 0 && value != 1) return BAKLAVA_EINVAL;
-      ctx->time_kernel = value == 1;
+      if (value < 0 || value > 2) return BAKLAVA_EINVAL;
+      if (ctx->ev_used && value != ctx->time_kernel) return BAKLAVA_ESTATE;  // read the pending record first
+      ctx->time_kernel = (int32_t)value;
       return BAKLAVA_OK;
     default:
       return BAKLAVA_EINVAL;

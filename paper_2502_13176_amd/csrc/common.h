@@ -183,7 +183,8 @@ void note_hip_error(hipError_t e);
 hipError_t launch_decode_valu(const DecodeParams& p, int dtype, int D, int n_items, hipStream_t s);
 // max_count: longest work item of the launch (rows); one_wave: the launch has at most one workgroup per
 // compute unit, so a workgroup may take the whole LDS (score tracking keeps its new scores there)
-hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, int max_count, bool one_wave, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeParams& p, int n_items, int max_count, bool one_wave, hipStream_t s,
+                              hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 hipError_t prepare_decode_mfma();
 // the weights of the calls on record, from the K rows alone (bf16, D = 128; needs only the lag_*,
 // k, score, items, G and scale fields)

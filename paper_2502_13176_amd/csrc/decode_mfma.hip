@@ -36,6 +36,8 @@
 // scores of a slab are read with the slab and the new values wait in LDS until the work item is
 // done, so the extra HBM writes (4 bytes per row) fall at the end of a launch instead of between
 // the K/V reads.
+#include <hip/hip_ext.h>
+
 #include "common.h"
 #include "decode_tail.h"
 
@@ -510,13 +512,19 @@ hipError_t prepare_decode_mfma() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, kFlushDynMax);
 }
 
-hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_count, bool one_wave, hipStream_t s) {
+// With a pair of events the kernel's own dispatch carries them: they take the time stamps of its
+// first and last wavefront, not those of commands placed around it on the stream.
+hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_count, bool one_wave, hipStream_t s,
+                              hipEvent_t ev0, hipEvent_t ev1) {
   if (n_items <= 0) return hipSuccess;
   if (p_in.G > 16) return hipErrorInvalidValue;
   DecodeParams p = p_in;
   p.ring_slots = 0;
+  const dim3 grid(n_items), block(64 * kWaves);
+  const bool timed = ev0 && ev1;
   if (!p.lag) {
-    decode_partial_mfma<false><<<dim3(n_items), dim3(64 * kWaves), 0, s>>>(p);
+    if (timed) hipExtLaunchKernelGGL(decode_partial_mfma<false>, grid, block, 0, s, ev0, ev1, 0, p);
+    else decode_partial_mfma<false><<<grid, block, 0, s>>>(p);
     return hipGetLastError();
   }
   // the LDS left beside the staging areas, split over the wavefronts; a launch of several waves of
@@ -526,7 +534,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p_in, int n_items, int max_cou
   const int need = ((max_count + kSlab - 1) / kSlab + kWaves - 1) / kWaves;  // slabs of the longest item per wavefront
   p.ring_slots = std::max(1, std::min(fit, need));
   const size_t dyn = (size_t)p.ring_slots * kWaves * slot_bytes;
-  decode_partial_mfma<true><<<dim3(n_items), dim3(64 * kWaves), dyn, s>>>(p);
+  if (timed) hipExtLaunchKernelGGL(decode_partial_mfma<true>, grid, block, dyn, s, ev0, ev1, 0, p);
+  else decode_partial_mfma<true><<<grid, block, dyn, s>>>(p);
   return hipGetLastError();
 }
 

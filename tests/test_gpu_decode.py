@@ -247,3 +247,45 @@ def test_stream_probe_modes():
         with pytest.raises(B.BaklavaError) as e:
             bad()
         assert e.value.status == B.EINVAL
+
+
+@pytest.mark.parametrize("kernel", [B.KERNEL_VALU, B.KERNEL_MFMA])
+@pytest.mark.parametrize("mode", [1, 2])
+def test_kernel_timing_record(kernel, mode):
+    """The measurement aid behind the roofline figure: both ways of timing the attention kernel count
+    every launch, report a positive time that a host clock around the same calls bounds from above,
+    leave the results alone, and the record is empty again after it has been read."""
+    import time
+    H = _h()
+    w = synth.shrink(synth.WORKLOADS["llama1"], name="timed", L=3, Hq=8, Hkv=2, batch=2, seed=43, slack=64)
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    arena = H.make_arena(w, [700, 300] * w.L, track=True)       # the tracked instance of the kernel is timed too
+    lens = [int(arena.cap_host[c]) - 1 - 37 * (c % 3) for c in range(arena.n_caches)]
+    st = H.fill_from_host(arena, w, lens, rng, scores="uniform")
+    arena.set_option(B.OPT_KERNEL, kernel)
+    H.set_chunk(arena, 256)
+    q, q64 = H.make_q(w, rng, w.L)
+    ref = H.gpu_decode(arena, w, q)
+    arena.set_option(B.OPT_TIME_KERNEL, mode)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    outs = [H.gpu_decode(arena, w, q) for _ in range(3)]           # one launch over all layers each
+    qd = H.to_device_storage(q, w.dtype, arena.device)
+    out_l = torch.empty((1, w.batch, w.Hq, w.D), dtype=torch.float32, device=arena.device)
+    for l in range(w.L):
+        arena.decode_attn(l, 1, qd[l:l + 1], out_l)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    with pytest.raises(B.BaklavaError) as e:                        # a record in one mode is read before the mode changes
+        arena.set_option(B.OPT_TIME_KERNEL, 3 - mode)
+    assert e.value.status == B.ESTATE
+    ms, launches = arena.profile_read()
+    assert launches == 3 + w.L and 0.0 < ms <= wall_ms
+    assert arena.profile_read() == (0.0, 0)
+    arena.set_option(B.OPT_TIME_KERNEL, 0)
+    for o in outs:
+        assert np.array_equal(o, ref)
+    H.check_decode_against_oracle(arena, w, st, q64, ref)
+    with pytest.raises(B.BaklavaError):
+        arena.set_option(B.OPT_TIME_KERNEL, 3)
+    arena.close()

@@ -196,7 +196,8 @@ enum {
                                    (baklava_profile_read): 1 = recorded on the stream before and
                                    after the launch, 2 = carried by the kernel's own dispatch (MFMA
                                    kernel; the other kernel is timed as under 1), 0 = off.  ESTATE
-                                   while timings taken in another mode are still unread            */
+                                   while timings taken in another mode are still unread.  A
+                                   measurement aid: leave it off while a stream is being captured  */
   BAKLAVA_OPT_CHUNK_TOKENS_WHOLE = 4, /* the same for launches over all layers at once               */
   BAKLAVA_OPT_TARGET_ITEMS = 5, /* > 0: launches over part of the layers lengthen their runs, layer by
                                    layer, until a layer has at most this many work items; 0: off.

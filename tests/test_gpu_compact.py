@@ -214,3 +214,52 @@ def test_caches_selected_tile_by_tile(scores, policy):
     after = run_compact_and_check(arena, w, after, policy=policy)                              # then both layers
     run_compact_and_check(arena, w, after, policy=policy)                                      # nothing left to evict
     arena.close()
+
+
+@pytest.mark.parametrize("seed", list(range(500, 512)))
+def test_seeded_random_evictions(seed):
+    """Random cache sizes on both sides of the threshold for tile-by-tile selection, random budgets, sink
+    and recent windows, live lengths and score distributions (continuous, few distinct values, all equal,
+    signed zeros, negative values), both policies, a random layer range first and all layers after it."""
+    H = _h()
+    r = np.random.Generator(np.random.PCG64(seed))
+    policy = B.POLICY_STREAMING if seed % 4 == 0 else B.POLICY_SCORE
+    L, Hkv, batch = int(r.integers(1, 4)), int(r.integers(1, 4)), int(r.integers(1, 3))
+    sink = int(r.integers(0, 6))
+    recent = 0 if policy == B.POLICY_STREAMING else int(r.integers(0, 40))
+    slack = int(r.choice([1, 50, 700, 9000]))
+    w = synth.shrink(synth.WORKLOADS["tiny"], name=f"evict{seed}", L=L, Hq=Hkv, Hkv=Hkv, batch=batch, seed=seed,
+                     sink=sink, recent=recent, slack=slack)
+    budgets = [int(max(sink + recent + 1, round(float(np.exp(r.uniform(np.log(16), np.log(30000))))))) for _ in range(L * Hkv)]
+    arena = H.make_arena(w, budgets, policy=policy)
+    threshold = int(r.choice([8192, 12000, 36864]))
+    arena.set_option(B.OPT_TILED_SELECT_ROWS, threshold)
+    cap = arena.cap_host
+    lens = [int(cap[c]) if r.random() < 0.3 else int(r.integers(0, int(cap[c]) + 1)) for c in range(arena.n_caches)]
+    st = H.fill_from_host(arena, w, lens, r, scores="uniform")
+    kind = str(r.choice(["uniform", "coarse", "equal", "signed_zero", "negative"]))
+    print(f"seed {seed}: policy={policy} L={L} Hkv={Hkv} batch={batch} sink={sink} recent={recent} slack={slack} "
+          f"threshold={threshold} scores={kind} budgets={budgets}", flush=True)
+    if kind != "uniform":
+        for c in range(arena.n_caches):
+            n = lens[c]
+            if n == 0:
+                continue
+            if kind == "equal":
+                s = np.full(n, 0.25, dtype=np.float32)
+            elif kind == "coarse":
+                s = (r.integers(0, 5, n) / 4).astype(np.float32)
+            elif kind == "negative":
+                s = (r.random(n) * 2 - 1).astype(np.float32)
+            else:
+                s = np.where(r.random(n) < 0.5, np.float32(0.0), np.float32(-0.0)).astype(np.float32)
+                s[r.integers(0, n, 8)] = r.random(8).astype(np.float32)
+            o = int(arena.off_host[c])
+            arena.score[o:o + n].copy_(torch.from_numpy(s).to(arena.device))
+            st.score[c] = s
+    lb = int(r.integers(0, L))
+    lc = int(r.integers(1, L - lb + 1))
+    after = run_compact_and_check(arena, w, st, policy=policy, layer_begin=lb, layer_count=lc)
+    after = run_compact_and_check(arena, w, after, policy=policy)
+    run_compact_and_check(arena, w, after, policy=policy, want_lists=False)
+    arena.close()

@@ -99,6 +99,34 @@ def test_invariants_on_the_benchmark_workloads(name):
         assert sum(1 for x in b if x == w.lo) >= round(w.floor_frac * w.m)
 
 
+@pytest.mark.parametrize("name", ["llama1", "llama32", "qwen", "long"])
+def test_benchmark_budgets_stay_close_to_exact_waterfilling(name):
+    """The budgets the benchmark workloads run on (and tests/golden stores), against the real-valued
+    shares clip(mu * I_i, lo, hi) that sum to the global budget, in exact rationals: clipped heads sit
+    exactly at their bound, every other head within the divisor rule's deviation of its share."""
+    w = synth.WORKLOADS[name]
+    imp = synth.importance_scores(w)
+    b = synth.budgets_for(w, O.alloc_proportional)
+    n_floor = int(round(w.floor_frac * w.m))
+    order = sorted(range(w.m), key=lambda i: (imp[i], i))
+    rest = sorted(order[n_floor:])                         # the heads that share what the pinned ones leave
+    assert all(b[i] == w.lo for i in order[:n_floor])
+    B = w.global_budget - n_floor * w.lo
+    sub = [b[i] for i in rest]
+    ideal = exact_waterfill([imp[i] for i in rest], B, w.lo, w.hi)
+    assert sum(sub) == B and sum(ideal) == B
+    free = [k for k in range(len(rest)) if w.lo < ideal[k] < w.hi]
+    wsum = sum(Fraction(imp[rest[k]]) for k in free)
+    for k, (bi, xi) in enumerate(zip(sub, ideal)):
+        if xi == w.hi:
+            assert bi in (w.hi, w.hi - 1)                  # the largest multiplier may stop one floor short of the bound
+        elif xi == w.lo:
+            assert bi == w.lo
+        else:
+            slack = 1 + len(rest) * Fraction(imp[rest[k]]) / wsum
+            assert abs(Fraction(bi) - xi) <= slack, (k, bi, float(xi))
+
+
 def test_expected_global_budgets():
     assert synth.WORKLOADS["llama1"].global_budget == 32768
     assert synth.WORKLOADS["llama32"].global_budget == 2516582
